@@ -1,0 +1,143 @@
+/*
+ * span_attn.h — C ABI of the span-restricted decode-attention library for MI355X (gfx950).
+ *
+ * The operation (paper Sec. 2.1, eqs. (4)-(6), for the single query row of the decoding
+ * phase; Sec. 3.2 "Token generation" and Sec. 3.3 restrict it to the self-selected span):
+ *
+ *   S_b        = union of the half-open position intervals of sequence b
+ *   s_j        = scale * q[b,h,:] . K[b,h,j,:]                       j in S_b
+ *   out[b,h,:] = sum_j softmax_j(s)_j * V[b,h,j,:]
+ *
+ * Only K / V rows inside the intervals are read.  The span is kept per sequence and shared by
+ * all heads (Sec. 3.3: separate metadata for each request of a batch; one kernel instance per
+ * head and batch item).
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory owned by the CALLER.  The library never
+ *     allocates, frees or keeps them.  "host" pointers are ordinary CPU memory.
+ *   - Work is enqueued on desc->stream; calls return without synchronising.
+ *   - Return value: 0 = OK; negative = argument / runtime error found on the host before
+ *     anything was launched (SPAN_ERR_*); positive = span-list validation class
+ *     (SPAN_BAD_*, only from span_validate).  Nothing throws or aborts across this ABI.
+ *   - Layouts, all contiguous: q and out [batch, heads, head_dim]; k_cache and v_cache
+ *     [batch, heads, max_len, head_dim] (a KV cache pre-allocated to its maximum length, Sec. 4),
+ *     so an interval of n positions is one run of n*head_dim elements per (batch, head).
+ *   - out is always fp32, whatever the input type.
+ */
+#ifndef SPAN_ATTN_H_
+#define SPAN_ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SPAN_F32 = 0, SPAN_F16 = 1, SPAN_BF16 = 2 } span_dtype_t;
+
+enum {
+  SPAN_OK = 0,
+  SPAN_ERR_NULL = -1,      /* a required pointer is NULL                                       */
+  SPAN_ERR_SHAPE = -2,     /* non-positive dimension, head_dim not 64 / 128, max_len > 2^22    */
+  SPAN_ERR_DTYPE = -3,     /* dtype is not a span_dtype_t                                      */
+  SPAN_ERR_WORKSPACE = -4, /* workspace missing, misaligned (256 B) or smaller than required   */
+  SPAN_ERR_HIP = -5,       /* a HIP call failed; see span_last_hip_error()                     */
+  SPAN_BAD_OFFSETS = 1,
+  SPAN_BAD_RANGE = 2,
+  SPAN_BAD_EMPTY_INTERVAL = 3,
+  SPAN_BAD_OVERLAP = 4,
+  SPAN_BAD_UNSORTED = 5,
+  SPAN_BAD_EMPTY_SPAN = 6
+};
+
+typedef struct span_attn_desc {
+  int32_t batch, heads;
+  int32_t head_dim;        /* 64 or 128                                                          */
+  int32_t max_len;         /* rows allocated per (batch, head) in the caches, <= 2^22            */
+  int32_t dtype;           /* span_dtype_t of q, k_cache, v_cache                                */
+  int32_t num_intervals;   /* entries held by span_starts / span_ends (span entry point only);
+                              interval indices are clamped to it on the device                  */
+  int32_t max_tokens;      /* upper bound on the attended positions of any one sequence (span
+                              tokens, or ctx_lens for the dense call); sizes the grid.
+                              0 = unknown, use max_len.  Positions beyond it are NOT attended.   */
+  int32_t num_splits;      /* 0 = let the library choose; > 0 = requested number of KV slices
+                              per (batch, head) (the library may raise it, see
+                              span_plan_splits)                                                  */
+  void* workspace;         /* device, 256-byte aligned, >= span_workspace_bytes(); may be NULL
+                              when that is 0                                                     */
+  size_t workspace_bytes;
+  void* stream;            /* hipStream_t; NULL = the default stream                             */
+} span_attn_desc_t;
+
+/*
+ * Decode attention over each sequence's span (Sec. 3.2-3.3; Algorithm 1 gives the same
+ * quantity block by block).
+ *   q, k_cache, v_cache : device, desc->dtype, layouts above
+ *   span_offsets        : device int32 [batch+1]; intervals of sequence b are
+ *                         offsets[b] .. offsets[b+1]-1
+ *   span_starts/ends    : device int32 [desc->num_intervals]; interval i covers positions
+ *                         [starts[i], ends[i])
+ *   ctx_lens            : device int32 [batch] or NULL.  Not needed to compute the result (the
+ *                         intervals say which rows are read); accepted for symmetry with the
+ *                         validator and ignored.
+ *   scale               : multiplies every score (1/sqrt(head_dim) in the paper, eq. (4))
+ *   out                 : device fp32 [batch, heads, head_dim]
+ * The list is expected to have passed span_validate, but the kernel is correct for any order of
+ * pairwise-disjoint intervals.  On a list that would not validate the result is unspecified, yet
+ * no row outside [0, max_len) of the sequence's own cache slab is read, and interval indices
+ * outside [0, num_intervals) are never read.  A sequence with no attended position gets an
+ * all-zero output row (never NaN).
+ */
+int span_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
+                     const int32_t* span_offsets, const int32_t* span_starts, const int32_t* span_ends,
+                     const int32_t* ctx_lens, float scale, float* out);
+
+/*
+ * Dense control: the same computation over S_b = [0, ctx_lens[b]) with no span metadata (decode
+ * attention as in Sec. 2.1 "Token generation"; plays the role of the dense baseline of Sec. 4).
+ *   ctx_lens : device int32 [batch]; values are clamped to [0, min(max_len, max_tokens)].
+ */
+int dense_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
+                      const int32_t* ctx_lens, float scale, float* out);
+
+/*
+ * Span-list validation on the HOST (all pointers are host memory; pure CPU).
+ * Sequences are scanned in index order; for a sequence its offsets are checked first, then its
+ * intervals in list order, each against the rules in this order; the first failure is returned,
+ * with *first_bad_seq and *first_bad_interval (index within the sequence's list, -1 when the
+ * failure is not tied to one interval) set; both are -1 on success.
+ *   SPAN_BAD_OFFSETS         offsets[0] != 0, offsets[b+1] < offsets[b] or offsets[b+1] > num_intervals
+ *   SPAN_BAD_RANGE           start < 0 or end > ctx_lens[b]
+ *   SPAN_BAD_EMPTY_INTERVAL  start >= end
+ *   SPAN_BAD_OVERLAP         start_i >= start_{i-1} and start_i < end_{i-1}
+ *   SPAN_BAD_UNSORTED        start_i < start_{i-1}
+ *   SPAN_BAD_EMPTY_SPAN      the sequence has no interval (softmax over nothing)
+ * Touching intervals (start_i == end_{i-1}) are legal.  span_tokens_per_seq (host int64 [batch],
+ * may be NULL) receives sum(end - start) of every sequence that was scanned without failure.
+ */
+int span_validate(int32_t batch, int32_t num_intervals, const int32_t* span_offsets, const int32_t* span_starts,
+                  const int32_t* span_ends, const int32_t* ctx_lens, int32_t* first_bad_seq,
+                  int32_t* first_bad_interval, int64_t* span_tokens_per_seq);
+
+/*
+ * How the library would partition the call described by desc: the number of KV slices per
+ * (batch, head) and the number of attended positions each slice owns.  One slice means the
+ * kernel writes `out` directly; more than one means partial softmax states go through the
+ * workspace and a second kernel merges them by log-sum-exp.  Pure host arithmetic.
+ */
+int span_plan_splits(const span_attn_desc_t* desc, int32_t* num_splits, int32_t* slice_tokens);
+
+/* Bytes of device workspace the call described by desc needs (0 when one slice is used). */
+size_t span_workspace_bytes(const span_attn_desc_t* desc);
+
+/* Static string for any code above. */
+const char* span_strerror(int code);
+
+/* The hipError_t (as int) of the last failed HIP call on this thread; 0 if none. */
+int span_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPAN_ATTN_H_ */

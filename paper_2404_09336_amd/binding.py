@@ -1,0 +1,178 @@
+"""ctypes binding with the same names as the C entry points of include/span_attn.h.
+
+Tensors are torch tensors that already live on the GPU; this module only checks their type and
+contiguity, fills the descriptor, and passes raw device pointers and the current HIP stream.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libspanattn.so")
+_lib = None
+
+SPAN_F32, SPAN_F16, SPAN_BF16 = 0, 1, 2
+
+
+class SpanAttnError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = int(code)
+        super().__init__(f"{where} failed with code {code}: {span_strerror(code)}")
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("max_len", ctypes.c_int32), ("dtype", ctypes.c_int32), ("num_intervals", ctypes.c_int32),
+                ("max_tokens", ctypes.c_int32), ("num_splits", ctypes.c_int32),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("stream", ctypes.c_void_p)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libspanattn.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+                               "`python -m paper_2404_09336_amd.build` (needs hipcc)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        P, I32, F = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
+        DP = ctypes.POINTER(_Desc)
+        lib.span_decode_attn.argtypes = [DP, P, P, P, P, P, P, P, F, P]
+        lib.span_decode_attn.restype = ctypes.c_int
+        lib.dense_decode_attn.argtypes = [DP, P, P, P, P, F, P]
+        lib.dense_decode_attn.restype = ctypes.c_int
+        lib.span_validate.argtypes = [I32, I32, P, P, P, P, P, P, P]
+        lib.span_validate.restype = ctypes.c_int
+        lib.span_plan_splits.argtypes = [DP, P, P]
+        lib.span_plan_splits.restype = ctypes.c_int
+        lib.span_workspace_bytes.argtypes = [DP]
+        lib.span_workspace_bytes.restype = ctypes.c_size_t
+        lib.span_strerror.argtypes = [ctypes.c_int]
+        lib.span_strerror.restype = ctypes.c_char_p
+        lib.span_last_hip_error.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def span_strerror(code: int) -> str:
+    return load_library().span_strerror(int(code)).decode()
+
+
+def _dtype_code(t):
+    import torch
+    try:
+        return {torch.float32: SPAN_F32, torch.float16: SPAN_F16, torch.bfloat16: SPAN_BF16}[t.dtype]
+    except KeyError:
+        raise TypeError(f"unsupported dtype {t.dtype}") from None
+
+
+def make_desc(batch, heads, head_dim, max_len, dtype_code, num_intervals=0, max_tokens=0, num_splits=0,
+              workspace_ptr=0, workspace_bytes=0, stream=0) -> _Desc:
+    return _Desc(batch, heads, head_dim, max_len, dtype_code, num_intervals, max_tokens, num_splits,
+                 workspace_ptr or None, workspace_bytes, stream or None)
+
+
+def span_plan_splits(desc: _Desc):
+    ns, st = ctypes.c_int32(), ctypes.c_int32()
+    rc = load_library().span_plan_splits(ctypes.byref(desc), ctypes.cast(ctypes.byref(ns), ctypes.c_void_p),
+                                         ctypes.cast(ctypes.byref(st), ctypes.c_void_p))
+    if rc != 0:
+        raise SpanAttnError(rc, "span_plan_splits")
+    return ns.value, st.value
+
+
+def span_workspace_bytes(desc: _Desc) -> int:
+    return int(load_library().span_workspace_bytes(ctypes.byref(desc)))
+
+
+def span_validate(span_offsets, span_starts, span_ends, ctx_lens):
+    """Host arrays in, (code, first_bad_seq, first_bad_interval, tokens_per_seq[int64]) out."""
+    off = np.ascontiguousarray(span_offsets, dtype=np.int32)
+    st = np.ascontiguousarray(span_starts, dtype=np.int32).reshape(-1)
+    en = np.ascontiguousarray(span_ends, dtype=np.int32).reshape(-1)
+    ctx = np.ascontiguousarray(ctx_lens, dtype=np.int32).reshape(-1)
+    if off.shape != (ctx.shape[0] + 1,) or st.shape != en.shape:
+        raise ValueError("span_offsets must have batch+1 entries and starts / ends equal lengths")
+    bs, bi = np.full(1, -7, np.int32), np.full(1, -7, np.int32)
+    tok = np.zeros(ctx.shape[0], dtype=np.int64)
+    vp = lambda a: ctypes.c_void_p(a.ctypes.data)
+    rc = load_library().span_validate(ctx.shape[0], st.shape[0], vp(off), vp(st), vp(en), vp(ctx), vp(bs), vp(bi),
+                                      vp(tok))
+    if rc < 0:
+        raise SpanAttnError(rc, "span_validate")
+    return int(rc), int(bs[0]), int(bi[0]), tok
+
+
+def _check_qkv(q, k_cache, v_cache):
+    if not (q.is_cuda and k_cache.is_cuda and v_cache.is_cuda):
+        raise ValueError("q, k_cache and v_cache must be GPU tensors")
+    if not (q.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous()):
+        raise ValueError("q, k_cache and v_cache must be contiguous")
+    B, H, L, D = k_cache.shape
+    if tuple(q.shape) != (B, H, D) or v_cache.shape != k_cache.shape:
+        raise ValueError("expected q [B,H,D] and k_cache / v_cache [B,H,L,D]")
+    if not (q.dtype == k_cache.dtype == v_cache.dtype):
+        raise ValueError("q, k_cache, v_cache must share one dtype")
+    return B, H, L, D
+
+
+def _i32_dev(t, n, name):
+    import torch
+    if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous() or t.numel() < n:
+        raise ValueError(f"{name} must be a contiguous int32 GPU tensor with at least {n} entries")
+    return t.data_ptr()
+
+
+def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, workspace, stream):
+    import torch
+    B, H, L, D = _check_qkv(q, k_cache, v_cache)
+    if out is None:
+        out = torch.empty((B, H, D), dtype=torch.float32, device=q.device)
+    elif out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous() or tuple(out.shape) != (B, H, D):
+        raise ValueError("out must be a contiguous fp32 GPU tensor [B,H,D]")
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    desc = make_desc(B, H, D, L, _dtype_code(q), num_intervals, int(max_tokens), int(num_splits), 0, 0, stream)
+    need = span_workspace_bytes(desc)
+    if need:
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        desc.workspace = workspace.data_ptr()
+        desc.workspace_bytes = workspace.numel() * workspace.element_size()
+    return desc, out, workspace
+
+
+def span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out=None, *,
+                     max_tokens=0, num_splits=0, workspace=None, stream=None):
+    """out[b,h,:] = softmax over the span's positions of scale*q.K, times V.  Returns `out` (fp32)."""
+    lib = load_library()
+    n_int = int(span_starts.numel())
+    desc, out, workspace = _prepare(q, k_cache, v_cache, out, n_int, max_tokens, num_splits, workspace, stream)
+    off_p = _i32_dev(span_offsets, desc.batch + 1, "span_offsets")
+    st_p = _i32_dev(span_starts, n_int, "span_starts")
+    en_p = _i32_dev(span_ends, n_int, "span_ends")
+    ctx_p = _i32_dev(ctx_lens, desc.batch, "ctx_lens") if ctx_lens is not None else None
+    rc = lib.span_decode_attn(ctypes.byref(desc), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), off_p, st_p,
+                              en_p, ctx_p, float(scale), out.data_ptr())
+    if rc != 0:
+        raise SpanAttnError(rc, "span_decode_attn")
+    return out
+
+
+def dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out=None, *, max_tokens=0, num_splits=0,
+                      workspace=None, stream=None):
+    """Dense control: every position below ctx_lens[b] is attended."""
+    lib = load_library()
+    desc, out, workspace = _prepare(q, k_cache, v_cache, out, 0, max_tokens, num_splits, workspace, stream)
+    ctx_p = _i32_dev(ctx_lens, desc.batch, "ctx_lens")
+    rc = lib.dense_decode_attn(ctypes.byref(desc), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), ctx_p,
+                               float(scale), out.data_ptr())
+    if rc != 0:
+        raise SpanAttnError(rc, "dense_decode_attn")
+    return out

@@ -1,0 +1,124 @@
+// Host-only parts of the span-attention library: span-list validation, work partitioning
+// arithmetic and error strings.  No GPU call in this file.
+#include <limits.h>
+
+#include "span_attn.h"
+#include "span_internal.h"
+
+extern "C" int span_validate(int32_t batch, int32_t num_intervals, const int32_t* span_offsets,
+                             const int32_t* span_starts, const int32_t* span_ends, const int32_t* ctx_lens,
+                             int32_t* first_bad_seq, int32_t* first_bad_interval, int64_t* span_tokens_per_seq) {
+  if (!span_offsets || !ctx_lens || !first_bad_seq || !first_bad_interval) return SPAN_ERR_NULL;
+  if (num_intervals > 0 && (!span_starts || !span_ends)) return SPAN_ERR_NULL;
+  if (batch < 0 || num_intervals < 0) return SPAN_ERR_SHAPE;
+  *first_bad_seq = -1;
+  *first_bad_interval = -1;
+  for (int32_t b = 0; b < batch; ++b) {
+    const int32_t first = span_offsets[b], last = span_offsets[b + 1];
+    auto fail = [&](int code, int32_t interval) {
+      *first_bad_seq = b;
+      *first_bad_interval = interval;
+      return code;
+    };
+    if (b == 0 && first != 0) return fail(SPAN_BAD_OFFSETS, -1);
+    if (last < first || last > num_intervals) return fail(SPAN_BAD_OFFSETS, -1);
+    if (last == first) return fail(SPAN_BAD_EMPTY_SPAN, -1);
+    int64_t tokens = 0;
+    int32_t prev_start = 0, prev_end = 0;
+    for (int32_t i = first; i < last; ++i) {
+      const int32_t s = span_starts[i], e = span_ends[i], k = i - first;
+      if (s < 0 || e > ctx_lens[b]) return fail(SPAN_BAD_RANGE, k);
+      if (s >= e) return fail(SPAN_BAD_EMPTY_INTERVAL, k);
+      if (k > 0) {
+        if (s < prev_start) return fail(SPAN_BAD_UNSORTED, k);
+        if (s < prev_end) return fail(SPAN_BAD_OVERLAP, k);
+      }
+      tokens += (int64_t)e - (int64_t)s;
+      prev_start = s;
+      prev_end = e;
+    }
+    if (span_tokens_per_seq) span_tokens_per_seq[b] = tokens;
+  }
+  return SPAN_OK;
+}
+
+namespace spanattn {
+
+int check_desc(const span_attn_desc_t* d) {
+  if (!d) return SPAN_ERR_NULL;
+  if (d->batch <= 0 || d->heads <= 0 || d->max_len <= 0 || d->max_len > kMaxLen) return SPAN_ERR_SHAPE;
+  if (d->head_dim != 64 && d->head_dim != 128) return SPAN_ERR_SHAPE;
+  if (d->num_intervals < 0 || d->max_tokens < 0 || d->num_splits < 0) return SPAN_ERR_SHAPE;
+  if ((int64_t)d->batch * d->heads > INT_MAX / 2) return SPAN_ERR_SHAPE;
+  if (d->heads > 65535 || d->batch > 65535) return SPAN_ERR_SHAPE;  // grid y / z limits
+  if (d->dtype != SPAN_F32 && d->dtype != SPAN_F16 && d->dtype != SPAN_BF16) return SPAN_ERR_DTYPE;
+  return SPAN_OK;
+}
+
+static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Slices are sized so that a call puts about kTargetWorkgroups workgroups on the chip (256 CUs x 8
+// resident workgroups), never fewer than kMinSlice positions per slice, never more than the
+// kMaxSlice the kernel's position table holds.
+Partition plan_partition(const span_attn_desc_t* d) {
+  const int64_t max_tok = (d->max_tokens > 0 && d->max_tokens < d->max_len) ? d->max_tokens : d->max_len;
+  const int64_t pairs = (int64_t)d->batch * d->heads;
+  int64_t splits = d->num_splits > 0 ? d->num_splits : ceil_div(kTargetWorkgroups, pairs);
+  const int64_t most = ceil_div(max_tok, kMinSlice);
+  if (d->num_splits == 0 && splits > most) splits = most;
+  if (splits > max_tok) splits = max_tok;
+  if (splits < 1) splits = 1;
+  int64_t slice = ceil_div(ceil_div(max_tok, splits), kSliceGranule) * kSliceGranule;
+  if (slice > kMaxSlice) slice = kMaxSlice;
+  splits = ceil_div(max_tok, slice);
+  Partition p;
+  p.num_splits = (int32_t)splits;
+  p.slice_tokens = (int32_t)slice;
+  p.max_tokens = (int32_t)max_tok;
+  return p;
+}
+
+size_t workspace_ml_bytes(const span_attn_desc_t* d, const Partition& p) {
+  const size_t n = (size_t)d->batch * d->heads * p.num_splits * 2 * sizeof(float);
+  return (n + 255) & ~(size_t)255;
+}
+
+size_t workspace_bytes(const span_attn_desc_t* d, const Partition& p) {
+  if (p.num_splits <= 1) return 0;
+  return workspace_ml_bytes(d, p) + (size_t)d->batch * d->heads * p.num_splits * d->head_dim * sizeof(float);
+}
+
+}  // namespace spanattn
+
+extern "C" int span_plan_splits(const span_attn_desc_t* desc, int32_t* num_splits, int32_t* slice_tokens) {
+  if (!num_splits || !slice_tokens) return SPAN_ERR_NULL;
+  const int rc = spanattn::check_desc(desc);
+  if (rc != SPAN_OK) return rc;
+  const spanattn::Partition p = spanattn::plan_partition(desc);
+  *num_splits = p.num_splits;
+  *slice_tokens = p.slice_tokens;
+  return SPAN_OK;
+}
+
+extern "C" size_t span_workspace_bytes(const span_attn_desc_t* desc) {
+  if (spanattn::check_desc(desc) != SPAN_OK) return 0;
+  return spanattn::workspace_bytes(desc, spanattn::plan_partition(desc));
+}
+
+extern "C" const char* span_strerror(int code) {
+  switch (code) {
+    case SPAN_OK: return "ok";
+    case SPAN_ERR_NULL: return "a required pointer is NULL";
+    case SPAN_ERR_SHAPE: return "unsupported shape (dims must be positive, head_dim 64 or 128, max_len <= 2^22)";
+    case SPAN_ERR_DTYPE: return "unsupported dtype";
+    case SPAN_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SPAN_ERR_HIP: return "a HIP call failed (see span_last_hip_error)";
+    case SPAN_BAD_OFFSETS: return "span_offsets must start at 0, not decrease, and stay within num_intervals";
+    case SPAN_BAD_RANGE: return "interval outside [0, ctx_len]";
+    case SPAN_BAD_EMPTY_INTERVAL: return "interval with start >= end";
+    case SPAN_BAD_OVERLAP: return "interval overlaps the previous one";
+    case SPAN_BAD_UNSORTED: return "interval starts before the previous one";
+    case SPAN_BAD_EMPTY_SPAN: return "sequence with no interval";
+    default: return "unknown code";
+  }
+}

@@ -1,0 +1,454 @@
+// Span-restricted single-query (decode) attention for gfx950: kernels and the two C entry points.
+//
+// What is computed: for every (batch b, head h), softmax over the scores of the positions in the
+// sequence's span only, times the matching V rows (paper Sec. 2.1 eqs. (4)-(6) for one query row,
+// restricted to the span as in Sec. 3.3).  The paper's own kernel visits fixed-size blocks that
+// touch the span and masks inside them (Algorithm 1); here the span is a list of half-open position
+// intervals, so exactly the rows inside the intervals are read and no mask exists.
+//
+// Mapping to the machine (single-query decode is a GEMV: one multiply-add per loaded element, so
+// the kernel is bound by HBM and uses no matrix cores):
+//   * grid = (KV slices, heads, batch).  A sequence's span is flattened into a virtual token index
+//     0..n_b-1 (prefix sums of the interval lengths); slice s owns virtual tokens [s*T, (s+1)*T).
+//     The host picks T so that short spans still give every CU several workgroups.
+//   * a workgroup is 4 wavefronts; each wavefront takes a contiguous quarter of the slice and is
+//     independent of the others until the final merge (it even builds its own part of the
+//     virtual-token -> position table, so no barrier sits in front of the first K load).
+//   * one 64-lane load instruction fetches 1 KiB = whole rows: D*sizeof(elt)/16 lanes per row, each
+//     lane a 128-bit piece.  The q.k dot product is finished with DPP adds inside those lanes; every
+//     row group of a wavefront carries its own online-softmax state (m, l, acc), merged by
+//     log-sum-exp at the end: first across row groups (shuffles), then across wavefronts (LDS), then
+//     - only if the call uses more than one slice - across slices by a second small kernel.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "span_attn.h"
+#include "span_internal.h"
+
+namespace spanattn {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = kWavesPerBlock * 64;
+constexpr int kRowsPerWaveMax = kMaxSlice / kWavesPerBlock;
+
+struct LaunchArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  float* out;
+  const int32_t* offsets;
+  const int32_t* starts;
+  const int32_t* ends;
+  const int32_t* ctx_lens;
+  float* part_ml;   // [batch*heads, num_splits, 2]  (m in log2 units, l)
+  float* part_acc;  // [batch*heads, num_splits, D]  un-normalised
+  int32_t heads, max_len, num_intervals, slice_tokens, num_splits, max_tokens;
+  float scale_log2e;
+};
+
+// ---- storage types: 16 bytes of a row -> fp32 --------------------------------------------------
+struct F32 {
+  static constexpr int kBytes = 4, kPerVec = 4;
+  static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t w = r[i];  // (bit_cast straight from a vector element reads element 0 every time)
+      f[i] = __builtin_bit_cast(float, w);
+    }
+  }
+};
+struct F16 {
+  static constexpr int kBytes = 2, kPerVec = 8;
+  static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t w = r[i];
+      const f16x2 h = __builtin_bit_cast(f16x2, w);
+      f[2 * i] = (float)h.x;
+      f[2 * i + 1] = (float)h.y;
+    }
+  }
+};
+struct BF16 {
+  static constexpr int kBytes = 2, kPerVec = 8;
+  static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t w = r[i];
+      f[2 * i] = __builtin_bit_cast(float, w << 16);
+      f[2 * i + 1] = __builtin_bit_cast(float, w & 0xffff0000u);
+    }
+  }
+};
+
+// ---- cross-lane helpers (wave64) ---------------------------------------------------------------
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), kCtrl, 0xf, 0xf, true));
+}
+template <int kCtrl>
+__device__ __forceinline__ int dpp_i(int x) {
+  return __builtin_amdgcn_update_dpp(0, x, kCtrl, 0xf, 0xf, true);
+}
+
+// Sum over each aligned group of kLanes lanes (8, 16 or 32); every lane of the group gets the sum.
+template <int kLanes>
+__device__ __forceinline__ float group_allreduce_sum(float x) {
+  x += dpp_f<0xB1>(x);                          // quad_perm [1,0,3,2]
+  x += dpp_f<0x4E>(x);                          // quad_perm [2,3,0,1]
+  if (kLanes >= 8) x += dpp_f<0x141>(x);        // row_half_mirror
+  if (kLanes >= 16) x += dpp_f<0x140>(x);       // row_mirror
+  if (kLanes >= 32) x += __shfl_xor(x, 16, 64);
+  return x;
+}
+
+// Inclusive prefix sum over the 64 lanes.
+__device__ __forceinline__ int wave_inclusive_scan(int x, int lane) {
+  x += dpp_i<0x111>(x);  // row_shr:1   (lanes without a source inside their row of 16 add 0)
+  x += dpp_i<0x112>(x);  // row_shr:2
+  x += dpp_i<0x114>(x);  // row_shr:4
+  x += dpp_i<0x118>(x);  // row_shr:8
+  const int t0 = __builtin_amdgcn_readlane(x, 15);
+  const int t1 = __builtin_amdgcn_readlane(x, 31);
+  const int t2 = __builtin_amdgcn_readlane(x, 47);
+  const int row = lane >> 4;
+  x += (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
+  return x;
+}
+
+__device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+__device__ __forceinline__ u32x4 load_row_piece(const char* slab, uint32_t byte_off) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(slab + byte_off));
+}
+
+// Merge two un-normalised softmax states held in log2 units.
+__device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int n, float m2, float l2,
+                                            const float* acc2) {
+  const float mn = fmaxf(m, m2);
+  const float ms = (mn == -INFINITY) ? 0.f : mn;
+  const float a = __builtin_amdgcn_exp2f(m - ms), b = __builtin_amdgcn_exp2f(m2 - ms);
+  l = l * a + l2 * b;
+  for (int i = 0; i < n; ++i) acc[i] = acc[i] * a + acc2[i] * b;
+  m = mn;
+}
+
+// ---- the streaming kernel ------------------------------------------------------------------------
+template <class Elt, int D, bool kDense, int U>
+__global__ __launch_bounds__(kThreads) void partial_kernel(const LaunchArgs a) {
+  constexpr int EPL = Elt::kPerVec;        // elements per lane (one 128-bit piece)
+  constexpr int LPR = D / EPL;             // lanes per row
+  constexpr int RPL = 64 / LPR;            // rows per wave-wide load
+  constexpr uint32_t ROWB = D * Elt::kBytes;
+  static_assert(LPR == 8 || LPR == 16 || LPR == 32, "row must span 8, 16 or 32 lanes");
+
+  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int grp = lane / LPR, lir = lane % LPR;
+  const size_t bh = (size_t)b * a.heads + h;
+
+  __shared__ int s_pos[kWavesPerBlock][kRowsPerWaveMax];
+  __shared__ int s_pref[kWavesPerBlock][64];
+  __shared__ int s_start[kWavesPerBlock][64];
+  __shared__ float s_acc[kWavesPerBlock][D];
+  __shared__ float s_ml[kWavesPerBlock][2];
+
+  // q piece of this lane, pre-multiplied by scale*log2(e) so that exp() becomes exp2().
+  float qf[EPL];
+  {
+    const u32x4 qr = *reinterpret_cast<const u32x4*>((const char*)a.q + bh * ROWB + (uint32_t)lir * 16u);
+    Elt::unpack(qr, qf);
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) qf[i] *= a.scale_log2e;
+  }
+
+  // ---- step 1: how many attended positions does the sequence have, which are mine ----------------
+  const int T = a.slice_tokens;
+  const int slice_begin = split * T;
+  int n_total;
+  int n_int = 0, off0 = 0;
+  int st0 = 0, len0 = 0, incl0 = 0;  // first chunk of 64 intervals, kept in registers
+  if (kDense) {
+    n_total = clampi(a.ctx_lens[b], 0, a.max_len);
+  } else {
+    off0 = clampi(a.offsets[b], 0, a.num_intervals);
+    const int off1 = clampi(a.offsets[b + 1], off0, a.num_intervals);
+    off0 = __builtin_amdgcn_readfirstlane(off0);
+    n_int = __builtin_amdgcn_readfirstlane(off1 - off0);
+    if (lane < n_int) {
+      st0 = a.starts[off0 + lane];
+      len0 = clampi(a.ends[off0 + lane] - st0, 0, a.max_len);
+    }
+    incl0 = wave_inclusive_scan(len0, lane);
+    n_total = __builtin_amdgcn_readlane(incl0, 63);
+    for (int c0 = 64; c0 < n_int && n_total < slice_begin + T; c0 += 64) {
+      int len = 0;
+      if (c0 + lane < n_int) len = clampi(a.ends[off0 + c0 + lane] - a.starts[off0 + c0 + lane], 0, a.max_len);
+      n_total += __builtin_amdgcn_readlane(wave_inclusive_scan(len, lane), 63);
+    }
+  }
+  n_total = n_total < a.max_tokens ? n_total : a.max_tokens;
+  const int cnt = __builtin_amdgcn_readfirstlane(clampi(n_total - slice_begin, 0, T));
+
+  if (cnt == 0) {  // nothing of this sequence falls into the slice (same decision in all 4 waves)
+    if (a.num_splits == 1) {
+      if (tid < D) a.out[bh * D + tid] = 0.f;
+    } else if (tid == 0) {
+      float* ml = a.part_ml + (bh * a.num_splits + split) * 2;
+      ml[0] = -INFINITY;
+      ml[1] = 0.f;
+    }
+    return;
+  }
+
+  // rows of the slice are dealt to the 4 waves in contiguous, RPL-aligned shares
+  const int rpw = (((cnt + kWavesPerBlock - 1) / kWavesPerBlock) + RPL - 1) / RPL * RPL;
+  const int wb = min(wave * rpw, cnt);
+  const int nrows = min(wb + rpw, cnt) - wb;
+  const int vbeg = slice_begin + wb;  // first virtual token of this wave
+
+  // ---- step 2: virtual token -> KV position for my rows (span path only) -----------------------
+  if (!kDense && nrows > 0) {
+    const int vend = vbeg + nrows;
+    int carry = 0;
+    for (int c0 = 0; c0 < n_int; c0 += 64) {
+      int st = st0, len = len0, incl = incl0;
+      if (c0 > 0) {
+        st = 0;
+        len = 0;
+        if (c0 + lane < n_int) {
+          st = a.starts[off0 + c0 + lane];
+          len = clampi(a.ends[off0 + c0 + lane] - st, 0, a.max_len);
+        }
+        incl = wave_inclusive_scan(len, lane);
+      }
+      const int chunk_total = __builtin_amdgcn_readlane(incl, 63);
+      if (carry + chunk_total > vbeg) {
+        // the chunk's exclusive prefixes and starts go to this wave's private LDS rows; the wave
+        // reads them back itself (LDS executes a wave's requests in order), so no block barrier
+        s_pref[wave][lane] = carry + incl - len;
+        s_start[wave][lane] = st;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int n_here = min(64, n_int - c0);
+        for (int r = lane; r < nrows; r += 64) {
+          const int v = vbeg + r;
+          if (v >= carry && v < carry + chunk_total) {
+            int idx = 0;  // last interval of the chunk whose exclusive prefix is <= v
+#pragma unroll
+            for (int step = 32; step > 0; step >>= 1) {
+              const int j = idx + step;
+              if (j < n_here && s_pref[wave][j] <= v) idx = j;
+            }
+            const int p = s_start[wave][idx] + (v - s_pref[wave][idx]);
+            s_pos[wave][r] = clampi(p, 0, a.max_len - 1);
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
+      carry += chunk_total;
+      if (carry >= vend) break;
+    }
+  }
+
+  // ---- step 3: stream my K and V rows, online softmax per row group ----------------------------
+  const char* kslab = (const char*)a.k + bh * (size_t)a.max_len * ROWB;
+  const char* vslab = (const char*)a.v + bh * (size_t)a.max_len * ROWB;
+  const uint32_t lane_off = (uint32_t)lir * 16u;
+
+  float m = -INFINITY, l = 0.f;
+  float acc[EPL];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+
+  for (int base = 0; base < nrows; base += RPL * U) {
+    u32x4 kr[U], vr[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int r = base + u * RPL + grp;
+      ok[u] = r < nrows;
+      const int rc = ok[u] ? r : nrows - 1;  // a row past the end re-reads the last one with weight 0
+      const int p = kDense ? (vbeg + rc) : s_pos[wave][rc];
+      const uint32_t off = (uint32_t)p * ROWB + lane_off;
+      kr[u] = load_row_piece(kslab, off);
+      vr[u] = load_row_piece(vslab, off);
+    }
+    float s[U];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL];
+      Elt::unpack(kr[u], kf);
+      float d = 0.f;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[i], d);
+      d = group_allreduce_sum<LPR>(d);
+      s[u] = ok[u] ? d : -INFINITY;
+      mx = fmaxf(mx, s[u]);
+    }
+    const float m_new = fmaxf(m, mx);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m - m_safe);
+    l *= alpha;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] *= alpha;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float p = __builtin_amdgcn_exp2f(s[u] - m_safe);
+      l += p;
+      float vf[EPL];
+      Elt::unpack(vr[u], vf);
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) acc[i] = fmaf(p, vf[i], acc[i]);
+    }
+    m = m_new;
+  }
+
+  // ---- step 4: merge row groups (shuffles), then waves (LDS) ------------------------------------
+#pragma unroll
+  for (int off = LPR; off < 64; off <<= 1) {
+    const float m2 = __shfl_xor(m, off, 64), l2 = __shfl_xor(l, off, 64);
+    float acc2[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc2[i] = __shfl_xor(acc[i], off, 64);
+    merge_state(m, l, acc, EPL, m2, l2, acc2);
+  }
+  if (lane < LPR) {
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) s_acc[wave][lir * EPL + i] = acc[i];
+    if (lane == 0) {
+      s_ml[wave][0] = m;
+      s_ml[wave][1] = l;
+    }
+  }
+  __syncthreads();
+  if (tid < D) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w)
+      if (s_ml[w][1] > 0.f) M = fmaxf(M, s_ml[w][0]);
+    float L = 0.f, o = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+      const float wgt = s_ml[w][1] > 0.f ? __builtin_amdgcn_exp2f(s_ml[w][0] - M) : 0.f;
+      L += wgt * s_ml[w][1];
+      o += wgt * s_acc[w][tid];
+    }
+    if (a.num_splits == 1) {
+      a.out[bh * D + tid] = L > 0.f ? o / L : 0.f;
+    } else {
+      const size_t slot = bh * a.num_splits + split;
+      a.part_acc[slot * D + tid] = o;
+      if (tid == 0) {
+        a.part_ml[slot * 2] = M;
+        a.part_ml[slot * 2 + 1] = L;
+      }
+    }
+  }
+}
+
+// ---- merge of the slices' states (only when num_splits > 1) --------------------------------------
+template <int D>
+__global__ __launch_bounds__(D) void merge_kernel(const LaunchArgs a) {
+  const size_t bh = (size_t)blockIdx.y * a.heads + blockIdx.x;
+  const int t = threadIdx.x;
+  const float* ml = a.part_ml + bh * a.num_splits * 2;
+  const float* pa = a.part_acc + bh * a.num_splits * D;
+  float M = -INFINITY;
+  for (int s = 0; s < a.num_splits; ++s)
+    if (ml[2 * s + 1] > 0.f) M = fmaxf(M, ml[2 * s]);
+  float L = 0.f, o = 0.f;
+  for (int s = 0; s < a.num_splits; ++s) {
+    const float ls = ml[2 * s + 1];
+    if (ls > 0.f) {
+      const float w = __builtin_amdgcn_exp2f(ml[2 * s] - M);
+      L += w * ls;
+      o += w * pa[(size_t)s * D + t];
+    }
+  }
+  a.out[bh * D + t] = L > 0.f ? o / L : 0.f;
+}
+
+thread_local int g_last_hip_error = 0;
+
+template <class Elt, int D, bool kDense>
+int launch_typed(const LaunchArgs& a, int batch, hipStream_t stream) {
+  const dim3 grid((unsigned)a.num_splits, (unsigned)a.heads, (unsigned)batch);
+  hipLaunchKernelGGL((partial_kernel<Elt, D, kDense, 4>), grid, dim3(kThreads), 0, stream, a);
+  if (a.num_splits > 1)
+    hipLaunchKernelGGL((merge_kernel<D>), dim3((unsigned)a.heads, (unsigned)batch), dim3(D), 0, stream, a);
+  const hipError_t err = hipGetLastError();
+  if (err != hipSuccess) {
+    g_last_hip_error = (int)err;
+    return SPAN_ERR_HIP;
+  }
+  return SPAN_OK;
+}
+
+template <bool kDense>
+int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* v, const int32_t* offsets,
+           const int32_t* starts, const int32_t* ends, const int32_t* ctx_lens, float scale, float* out) {
+  const int rc = check_desc(d);
+  if (rc != SPAN_OK) return rc;
+  if (!q || !k || !v || !out) return SPAN_ERR_NULL;
+  if (kDense ? !ctx_lens : (!offsets || (d->num_intervals > 0 && (!starts || !ends)))) return SPAN_ERR_NULL;
+  const Partition p = plan_partition(d);
+  const size_t need = workspace_bytes(d, p);
+  if (need > 0 && (!d->workspace || ((uintptr_t)d->workspace & 255u) || d->workspace_bytes < need))
+    return SPAN_ERR_WORKSPACE;
+
+  LaunchArgs a;
+  a.q = q;
+  a.k = k;
+  a.v = v;
+  a.out = out;
+  a.offsets = offsets;
+  a.starts = starts;
+  a.ends = ends;
+  a.ctx_lens = ctx_lens;
+  a.part_ml = need ? (float*)d->workspace : nullptr;
+  a.part_acc = need ? (float*)((char*)d->workspace + workspace_ml_bytes(d, p)) : nullptr;
+  a.heads = d->heads;
+  a.max_len = d->max_len;
+  a.num_intervals = d->num_intervals;
+  a.slice_tokens = p.slice_tokens;
+  a.num_splits = p.num_splits;
+  a.max_tokens = p.max_tokens;
+  a.scale_log2e = scale * 1.4426950408889634f;
+  hipStream_t stream = (hipStream_t)d->stream;
+
+  const bool d128 = d->head_dim == 128;
+  switch (d->dtype) {
+    case SPAN_F32:
+      return d128 ? launch_typed<F32, 128, kDense>(a, d->batch, stream) : launch_typed<F32, 64, kDense>(a, d->batch, stream);
+    case SPAN_F16:
+      return d128 ? launch_typed<F16, 128, kDense>(a, d->batch, stream) : launch_typed<F16, 64, kDense>(a, d->batch, stream);
+    default:
+      return d128 ? launch_typed<BF16, 128, kDense>(a, d->batch, stream) : launch_typed<BF16, 64, kDense>(a, d->batch, stream);
+  }
+}
+
+}  // namespace
+}  // namespace spanattn
+
+extern "C" int span_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_cache,
+                                const void* v_cache, const int32_t* span_offsets, const int32_t* span_starts,
+                                const int32_t* span_ends, const int32_t* ctx_lens, float scale, float* out) {
+  (void)ctx_lens;
+  return spanattn::launch<false>(desc, q, k_cache, v_cache, span_offsets, span_starts, span_ends, nullptr, scale, out);
+}
+
+extern "C" int dense_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_cache,
+                                 const void* v_cache, const int32_t* ctx_lens, float scale, float* out) {
+  return spanattn::launch<true>(desc, q, k_cache, v_cache, nullptr, nullptr, nullptr, ctx_lens, scale, out);
+}
+
+extern "C" int span_last_hip_error(void) { return spanattn::g_last_hip_error; }

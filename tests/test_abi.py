@@ -1,0 +1,143 @@
+"""Host-side checks of the C-ABI library that need no GPU: exported symbols, argument checking,
+work-partition arithmetic, and the validator against the oracle's (bit-exact)."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2404_09336_amd as span
+from paper_2404_09336_amd import binding
+from test_oracle_validate import load_golden
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "span_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(span_\w+|dense_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = span.load_library()
+    names = declared_functions()
+    assert {"span_decode_attn", "dense_decode_attn", "span_validate", "span_plan_splits", "span_workspace_bytes",
+            "span_strerror", "span_last_hip_error"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_strerror_covers_all_codes():
+    seen = set()
+    for code in range(-5, 7):
+        s = span.span_strerror(code)
+        assert s and s != "unknown code"
+        seen.add(s)
+    assert len(seen) == 12
+    assert span.span_strerror(99) == "unknown code"
+
+
+def _call_span(desc, ptrs=(1, 1, 1, 1, 1, 1, 1, 1)):
+    lib = span.load_library()
+    q, k, v, off, st, en, ctx, out = [ctypes.c_void_p(p) if p else None for p in ptrs]
+    return lib.span_decode_attn(ctypes.byref(desc) if desc is not None else None, q, k, v, off, st, en, ctx, 0.1, out)
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    ok = dict(batch=2, heads=4, head_dim=128, max_len=64, dtype_code=1, num_intervals=4)
+    mk = lambda **kw: binding.make_desc(**{**ok, **kw})
+    assert _call_span(None) == -1
+    assert _call_span(mk(), ptrs=(0, 1, 1, 1, 1, 1, 1, 1)) == -1
+    assert _call_span(mk(), ptrs=(1, 1, 1, 0, 1, 1, 1, 1)) == -1
+    assert _call_span(mk(), ptrs=(1, 1, 1, 1, 1, 1, 1, 0)) == -1
+    assert _call_span(mk(head_dim=96)) == -2
+    assert _call_span(mk(batch=0)) == -2
+    assert _call_span(mk(max_len=(1 << 22) + 1)) == -2
+    assert _call_span(mk(dtype_code=7)) == -3
+    # several slices but no workspace / a short one / a misaligned one
+    need = span.span_workspace_bytes(mk(num_splits=2))
+    assert need > 0
+    assert _call_span(mk(num_splits=2)) == -4
+    assert _call_span(mk(num_splits=2, workspace_ptr=4096, workspace_bytes=need - 1)) == -4
+    assert _call_span(mk(num_splits=2, workspace_ptr=4096 + 64, workspace_bytes=need)) == -4
+    lib = span.load_library()
+    assert lib.dense_decode_attn(ctypes.byref(mk()), 1, 1, 1, None, 0.1, 1) == -1
+    assert lib.dense_decode_attn(ctypes.byref(mk(head_dim=32)), 1, 1, 1, 1, 0.1, 1) == -2
+
+
+def test_partition_arithmetic():
+    for B, H, L, mt, ns in itertools.product([1, 8, 64, 300], [1, 32], [1, 100, 512, 4096, 16384, 1 << 22],
+                                             [0, 1, 63, 157, 5000], [0, 1, 2, 5, 64]):
+        d = binding.make_desc(B, H, 128, L, 1, 10, mt, ns)
+        splits, slice_tokens = span.span_plan_splits(d)
+        max_tok = min(mt, L) if mt > 0 else L
+        assert 1 <= slice_tokens <= 1024
+        assert splits * slice_tokens >= max_tok              # every position has an owner
+        assert (splits - 1) * slice_tokens < max_tok         # and no slice is useless
+        if ns and -(-max_tok // ns) <= 1024 - 16 and ns <= max_tok:
+            assert splits <= ns
+        ws = span.span_workspace_bytes(d)
+        assert (ws == 0) == (splits == 1)
+        if splits > 1:
+            assert ws >= B * H * splits * (128 + 2) * 4
+
+
+def test_validator_matches_oracle_on_golden_cases():
+    for ctx, off, st, en, exp in load_golden():
+        got = span.span_validate(off, st, en, ctx)
+        assert got[:3] == exp
+        ref = oracle.validate(off, st, en, ctx)
+        assert got[:3] == ref[:3]
+
+
+def test_validator_bit_exact_exhaustive_tiny():
+    pts = range(-1, 5)
+    pairs = list(itertools.product(pts, pts))
+    for k in range(0, 4):
+        for combo in itertools.product(pairs, repeat=k):
+            st = [c[0] for c in combo]
+            en = [c[1] for c in combo]
+            got = span.span_validate([0, k], st, en, [3])
+            ref = oracle.validate([0, k], st, en, [3])
+            assert got[:3] == ref[:3], (st, en)
+            if got[0] == 0:
+                assert np.array_equal(got[3], ref[3])
+
+
+def test_validator_bit_exact_random_batches():
+    rng = np.random.default_rng(7)
+    from workloads import CONFIGS, draw_spans
+    for trial in range(300):
+        cfg = CONFIGS[int(rng.choice([1, 2, 3, 4]))]
+        sp = draw_spans(cfg, seed=1000 + trial)
+        off, st, en, ctx = sp.offsets.copy(), sp.starts.copy(), sp.ends.copy(), sp.ctx_lens.copy()
+        kind = trial % 6
+        i = int(rng.integers(0, st.shape[0]))
+        b = int(rng.integers(0, ctx.shape[0]))
+        if kind == 1:
+            st[i] = en[i] + int(rng.integers(0, 3))
+        elif kind == 2:
+            en[i] = ctx.max() + int(rng.integers(1, 50))
+        elif kind == 3:
+            j = int(rng.integers(0, st.shape[0]))
+            st[[i, j]] = st[[j, i]]
+            en[[i, j]] = en[[j, i]]
+        elif kind == 4:
+            off[b + 1] = off[b] + int(rng.integers(-2, 1))
+        elif kind == 5:
+            st[i] = st[i] - int(rng.integers(1, 40))
+        got = span.span_validate(off, st, en, ctx)
+        ref = oracle.validate(off, st, en, ctx)
+        assert got[:3] == ref[:3], (trial, kind)
+        if got[0] == 0:
+            assert np.array_equal(got[3], ref[3])
+
+
+def test_validator_offsets_two_sequences_exhaustive():
+    st, en = [0, 2, 1], [1, 3, 2]
+    for off in itertools.product(range(-1, 5), repeat=3):
+        assert span.span_validate(list(off), st, en, [3, 3])[:3] == oracle.validate(list(off), st, en, [3, 3])[:3]

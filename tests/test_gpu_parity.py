@@ -1,0 +1,248 @@
+"""Parity of the HIP path (through the C ABI) against the fp64 oracle, element by element, on the same
+seeded inputs.  Tolerances: max-abs 1e-5 for fp32 inputs, 2e-3 for fp16 / bf16 inputs (fp32 accumulation,
+fp32 output)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2404_09336_amd as span
+from workloads import (CONFIGS, DecodeConfig, SpanBatch, draw_qkv, draw_spans, full_cover_spans, microbench_spans,
+                       to_host_raw)
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}
+
+
+def _dev(a, device):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def run_span(cfg, sp, q, K, V, device, **kw):
+    code, bs, bi, tok = span.span_validate(sp.offsets, sp.starts, sp.ends, sp.ctx_lens)
+    kw.setdefault("max_tokens", int(tok.max()) if code == 0 and len(tok) else 0)
+    out = span.span_decode_attn(q, K, V, _dev(sp.offsets, device), _dev(sp.starts, device), _dev(sp.ends, device),
+                                _dev(sp.ctx_lens, device), np.float32(cfg.scale), **kw)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+def run_dense(cfg, ctx_lens, q, K, V, device, **kw):
+    out = span.dense_decode_attn(q, K, V, _dev(np.asarray(ctx_lens, np.int32), device), np.float32(cfg.scale), **kw)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+def oracle_span(cfg, sp, q, K, V):
+    return oracle.span_attn(to_host_raw(q), to_host_raw(K), to_host_raw(V), sp.offsets, sp.starts, sp.ends,
+                            np.float32(cfg.scale), dtype=cfg.dtype)
+
+
+def oracle_dense(cfg, ctx_lens, q, K, V):
+    return oracle.dense_attn(to_host_raw(q), to_host_raw(K), to_host_raw(V), ctx_lens, np.float32(cfg.scale),
+                             dtype=cfg.dtype)
+
+
+def check(got, ref, tol, what):
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = float(np.abs(got - ref).max())
+    print(f"[parity] {what}: max-abs err {err:.3e} (tol {tol:g})", flush=True)
+    assert err <= tol, f"{what}: max-abs err {err:.3e} > {tol:g}"
+
+
+def small_cfg(dtype, D, B=3, H=5, L=700, min_len=None, cid=90):
+    return DecodeConfig(cid, f"small-{dtype}-{D}", B, H, D, L, L if min_len is None else min_len, dtype, TOL[dtype])
+
+
+# ------------------------------------------------------------------ the five workloads, full size
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+def test_workload_span_parity(cid, gpu_device):
+    cfg = CONFIGS[cid]
+    sp = draw_spans(cfg)
+    assert span.span_validate(sp.offsets, sp.starts, sp.ends, sp.ctx_lens)[0] == 0
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device)
+    got = run_span(cfg, sp, q, K, V, gpu_device)
+    check(got, oracle_span(cfg, sp, q, K, V), cfg.tol, f"config {cid} span (coverage {sp.coverage():.3f})")
+    # without the caller's bound on span tokens the grid is sized for max_len: same result
+    got2 = run_span(cfg, sp, q, K, V, gpu_device, max_tokens=0)
+    check(got2, got, 1e-6, f"config {cid} span, max_tokens unknown vs known")
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+def test_workload_dense_parity(cid, gpu_device):
+    cfg = CONFIGS[cid]
+    sp = draw_spans(cfg)
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device)
+    ref = oracle_dense(cfg, sp.ctx_lens, q, K, V)
+    check(run_dense(cfg, sp.ctx_lens, q, K, V, gpu_device), ref, cfg.tol, f"config {cid} dense")
+    # dense attention sent through the span path as one interval [0, len) (Sec. 4.1 control)
+    full = full_cover_spans(sp.ctx_lens)
+    check(run_span(cfg, full, q, K, V, gpu_device), ref, cfg.tol, f"config {cid} full-cover span vs dense oracle")
+
+
+def test_stress_uniform_coverages(gpu_device):
+    cfg = CONFIGS[5]
+    base = draw_spans(cfg)
+    q, K, V = draw_qkv(cfg, base.ctx_lens, device=gpu_device)
+    hq, hK, hV = to_host_raw(q), to_host_raw(K), to_host_raw(V)
+    for c in (0.05, 0.10, 0.25, 0.50):
+        sp = draw_spans(cfg, coverage=c)          # same seed -> same ctx_lens as `base`
+        assert np.array_equal(sp.ctx_lens, base.ctx_lens)
+        ref = oracle.span_attn(hq, hK, hV, sp.offsets, sp.starts, sp.ends, np.float32(cfg.scale), dtype=cfg.dtype)
+        check(run_span(cfg, sp, q, K, V, gpu_device), ref, cfg.tol, f"config 5 coverage {c}")
+
+
+# ------------------------------------------------------------------ every (dtype, head_dim) kernel
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("D", [64, 128])
+def test_all_kernel_instances(dtype, D, gpu_device):
+    cfg = small_cfg(dtype, D, min_len=300)
+    rng = np.random.default_rng(5 + D)
+    ctx = rng.integers(cfg.min_len, cfg.max_len + 1, size=cfg.batch).astype(np.int32)
+    per_seq = []
+    for b in range(cfg.batch):
+        cuts = np.sort(rng.choice(np.arange(0, ctx[b] + 1), size=12, replace=False))
+        per_seq.append([(int(cuts[i]), int(cuts[i + 1])) for i in range(0, 12, 2)])
+    sp = SpanBatch.from_lists(per_seq, ctx)
+    q, K, V = draw_qkv(cfg, ctx, device=gpu_device, seed=77)
+    ref = oracle_span(cfg, sp, q, K, V)
+    for ns in (0, 1, 2, 5):
+        check(run_span(cfg, sp, q, K, V, gpu_device, num_splits=ns), ref, cfg.tol, f"{dtype} D={D} splits={ns}")
+    dref = oracle_dense(cfg, ctx, q, K, V)
+    for ns in (0, 1, 3):
+        check(run_dense(cfg, ctx, q, K, V, gpu_device, num_splits=ns), dref, cfg.tol, f"{dtype} D={D} dense splits={ns}")
+
+
+# ------------------------------------------------------------------ split-KV partition and merge
+def test_forced_split_counts_agree_with_oracle(gpu_device):
+    cfg = small_cfg("f16", 128, B=2, H=3, L=3000)
+    sp = SpanBatch.from_lists([[(0, 700), (1000, 1001), (1500, 2600)], [(5, 9), (2990, 3000)]], [3000, 3000])
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=3)
+    ref = oracle_span(cfg, sp, q, K, V)
+    for ns in (1, 2, 3, 4, 7, 13, 29, 113):
+        check(run_span(cfg, sp, q, K, V, gpu_device, num_splits=ns), ref, cfg.tol, f"splits={ns}")
+
+
+def test_caller_workspace_is_used_and_sufficient(gpu_device):
+    from paper_2404_09336_amd import binding
+    cfg = small_cfg("f16", 128, B=2, H=2, L=512)
+    sp = full_cover_spans([512, 300])
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=4)
+    d = binding.make_desc(2, 2, 128, 512, 1, 2, 0, 4)
+    need = span.span_workspace_bytes(d)
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=gpu_device)   # NaN bit patterns everywhere
+    got = run_span(cfg, sp, q, K, V, gpu_device, num_splits=4, max_tokens=0, workspace=ws)
+    check(got, oracle_span(cfg, sp, q, K, V), cfg.tol, "caller workspace pre-filled with 0xFF")
+
+
+# ------------------------------------------------------------------ degenerate and edge cases
+def test_single_position_returns_v_row(gpu_device):
+    for dtype in ("f32", "f16", "bf16"):
+        cfg = small_cfg(dtype, 128, B=4, H=2, L=130)
+        sp = SpanBatch.from_lists([[(0, 1)], [(129, 130)], [(64, 65)], [(17, 18)]], [130] * 4)
+        q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=5)
+        got = run_span(cfg, sp, q, K, V, gpu_device)
+        for b, pos in enumerate((0, 129, 64, 17)):
+            assert np.array_equal(got[b], V[b, :, pos].float().cpu().numpy().astype(np.float64)), (dtype, b)
+
+
+def test_empty_span_gives_zero_rows(gpu_device):
+    cfg = small_cfg("f16", 128, B=3, H=2, L=64)
+    sp = SpanBatch.from_lists([[(3, 9)], [], [(60, 64)]], [64, 64, 64])
+    assert span.span_validate(sp.offsets, sp.starts, sp.ends, sp.ctx_lens)[:2] == (6, 1)
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=6)
+    for ns in (1, 2):
+        got = run_span(cfg, sp, q, K, V, gpu_device, num_splits=ns, max_tokens=0)
+        assert not got[1].any()
+        check(got, oracle_span(cfg, sp, q, K, V), cfg.tol, f"batch with an empty span, splits={ns}")
+
+
+def test_span_sizes_1_to_40_and_ragged_tails(gpu_device):
+    for dtype, D in (("f16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)):
+        cfg = small_cfg(dtype, D, B=40, H=2, L=96)
+        per_seq = [[(5, 5 + n)] if n % 2 else [(0, (n + 1) // 2), (50, 50 + n // 2)] for n in range(1, 41)]
+        sp = SpanBatch.from_lists(per_seq, [96] * 40)
+        q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=7)
+        check(run_span(cfg, sp, q, K, V, gpu_device), oracle_span(cfg, sp, q, K, V), cfg.tol, f"n=1..40 {dtype} D={D}")
+        ctx = np.arange(1, 41, dtype=np.int32)
+        check(run_dense(cfg, ctx, q, K, V, gpu_device), oracle_dense(cfg, ctx, q, K, V), cfg.tol,
+              f"dense len=1..40 {dtype} D={D}")
+
+
+def test_interval_order_and_split_invariance(gpu_device):
+    cfg = small_cfg("f16", 128, B=1, H=4, L=1200)
+    iv = [(0, 64), (100, 113), (113, 300), (512, 1000), (1190, 1200)]
+    q, K, V = draw_qkv(cfg, [1200], device=gpu_device, seed=8)
+    base_sp = SpanBatch.from_lists([iv], [1200])
+    ref = oracle_span(cfg, base_sp, q, K, V)
+    base = run_span(cfg, base_sp, q, K, V, gpu_device)
+    check(base, ref, cfg.tol, "sorted list")
+    rng = np.random.default_rng(9)
+    for _ in range(4):
+        perm = [iv[i] for i in rng.permutation(len(iv))]
+        got = run_span(cfg, SpanBatch.from_lists([perm], [1200]), q, K, V, gpu_device, max_tokens=0)
+        check(got, ref, cfg.tol, f"permuted list {perm}")
+    pieces = [(0, 10), (10, 64), (100, 113), (113, 200), (200, 300), (512, 513), (513, 1000), (1190, 1200)]
+    got = run_span(cfg, SpanBatch.from_lists([pieces], [1200]), q, K, V, gpu_device)
+    check(got, ref, cfg.tol, "intervals split into touching pieces")
+
+
+def test_many_intervals_per_sequence(gpu_device):
+    """More than 64 intervals per sequence (several metadata chunks), including single-token intervals."""
+    cfg = small_cfg("bf16", 128, B=3, H=2, L=4096)
+    rng = np.random.default_rng(10)
+    per_seq = []
+    for k in (65, 200, 1000):
+        lens = rng.integers(1, 4, size=k)
+        from workloads import place_disjoint
+        per_seq.append(place_disjoint(rng, lens, 0, 4096))
+    sp = SpanBatch.from_lists(per_seq, [4096] * 3)
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=11)
+    ref = oracle_span(cfg, sp, q, K, V)
+    for ns in (0, 1, 3):
+        check(run_span(cfg, sp, q, K, V, gpu_device, num_splits=ns), ref, cfg.tol, f"65/200/1000 intervals splits={ns}")
+
+
+def test_largest_slice_and_max_tokens_bound(gpu_device):
+    """One (batch, head) pair per workgroup with the largest slice the kernel supports (1024 positions)."""
+    cfg = small_cfg("f16", 128, B=2, H=2, L=2048)
+    sp = SpanBatch.from_lists([[(0, 1024)], [(1000, 2023)]], [2048, 2048])
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=12)
+    check(run_span(cfg, sp, q, K, V, gpu_device, num_splits=1), oracle_span(cfg, sp, q, K, V), cfg.tol, "slice of 1024")
+
+
+def test_rows_outside_span_never_reach_output(gpu_device):
+    cfg = small_cfg("f16", 128, B=2, H=2, L=256)
+    sp = SpanBatch.from_lists([[(10, 20), (100, 140)], [(0, 3), (250, 256)]], [256, 256])
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=13)
+    ref = oracle_span(cfg, sp, q, K, V)
+    keep = torch.zeros((2, 256), dtype=torch.bool, device=gpu_device)
+    for b in range(2):
+        for s, e in sp.intervals(b):
+            keep[b, s:e] = True
+    K2, V2 = K.clone(), V.clone()
+    K2.masked_fill_(~keep[:, None, :, None], float("nan"))
+    V2.masked_fill_(~keep[:, None, :, None], float("inf"))
+    check(run_span(cfg, sp, q, K2, V2, gpu_device), ref, cfg.tol, "NaN / Inf outside the span")
+
+
+def test_microbenchmark_masks(gpu_device):
+    """Masks of the paper's kernel micro-benchmark (Sec. 5.2): 50 % of the context kept in runs."""
+    cfg = DecodeConfig(91, "microbench", 4, 32, 128, 2048, 2048, "f16", 2e-3)
+    q, K, V = draw_qkv(cfg, [2048] * 4, device=gpu_device, seed=14)
+    for sbs in (32, 64, 128, 256):
+        sp = microbench_spans(4, 2048, sbs, seed=sbs)
+        check(run_span(cfg, sp, q, K, V, gpu_device), oracle_span(cfg, sp, q, K, V), cfg.tol, f"sparsity block {sbs}")
+
+
+def test_non_default_stream(gpu_device):
+    cfg = small_cfg("f16", 128, B=2, H=4, L=512)
+    sp = SpanBatch.from_lists([[(0, 100), (400, 512)], [(7, 300)]], [512, 512])
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=15)
+    ref = oracle_span(cfg, sp, q, K, V)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream(device=gpu_device)
+    with torch.cuda.stream(s):
+        got = run_span(cfg, sp, q, K, V, gpu_device, num_splits=3)
+    check(got, ref, cfg.tol, "side stream")

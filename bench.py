@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of span-restricted decode attention on one MI355X.
+
+A "step" is one span_decode_attn call (all of: locate work, q.K scores, online softmax, p.V, merge)
+over one batch of synthetic input that is already resident in HBM.  The headline workload is the
+arithmetic-evaluation-shaped one (config 3: batch 64, 32 heads x 128, 512 cached tokens, ~30 % of them
+in the span, fp16).  Steps rotate over several independent (K, V, span) copies so that the bytes touched
+between two uses of a buffer exceed the on-package cache: the figure is HBM bandwidth, not cache bandwidth.
+
+Prints ONE JSON line:
+  value    = span bytes (K and V rows inside the intervals) * steps / wall time of the timed region  [GB/s]
+  roofline = same bytes / average call duration from HIP events on the launch stream, against 8 TB/s
+  cpu_baseline = the fp64 CPU oracle on the same workload, timed on the host cores
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E, published peak
+LLC_BYTES = 256 * 1024 * 1024    # on-package last-level cache to defeat by rotation
+PAPER_CONTEXT = {"gain": "up to 28% more tokens/s end to end (27.7% at 1536-1792 output tokens)",
+                 "hardware": "1x NVIDIA A100 80GB, LLaMA-7B, batch 48", "source": "paper abstract and Sec. 4.1"}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4000)
+    ap.add_argument("--warmup", type=int, default=400)
+    ap.add_argument("--config", type=int, default=3, help="workload id 1..5 (headline: 3)")
+    ap.add_argument("--copies", type=int, default=0, help="independent KV copies to rotate over (0 = auto)")
+    ap.add_argument("--coverage", type=float, default=None, help="config 5 only: uniform span coverage")
+    ap.add_argument("--num-splits", type=int, default=0)
+    ap.add_argument("--only", choices=["all", "span", "dense"], default="all",
+                    help="'span' / 'dense' run just that timed loop (for profiling one kernel)")
+    ap.add_argument("--others", action="store_true", help="also time configs 2, 4, 5 (reported under 'workloads')")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy (reference point for HBM traffic counters)")
+    return ap.parse_args()
+
+
+class Workload:
+    """`copies` independent instances of one config: tensors on the GPU plus prepared calls."""
+
+    def __init__(self, cfg_id, copies, device, coverage=None, num_splits=0):
+        import numpy as np
+        import torch
+        import paper_2404_09336_amd as span
+        from workloads import CONFIGS, draw_qkv, draw_spans
+        self.cfg = cfg = CONFIGS[cfg_id]
+        self.span_calls, self.dense_calls = [], []
+        self.span_bytes, self.dense_bytes, self.coverages = [], [], []
+        self.host = []
+        row_pair = 2 * cfg.head_dim * cfg.elt_bytes * cfg.heads     # K and V bytes per position, all heads
+        for c in range(copies):
+            sp = draw_spans(cfg, seed=cfg.seed(c), coverage=coverage)
+            code, _, _, tok = span.span_validate(sp.offsets, sp.starts, sp.ends, sp.ctx_lens)
+            assert code == 0, code
+            q, K, V = draw_qkv(cfg, sp.ctx_lens, seed=cfg.seed(c), device=device)
+            dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
+            off, st, en, ctx = dev(sp.offsets), dev(sp.starts), dev(sp.ends), dev(sp.ctx_lens)
+            self.span_calls.append(span.prepare_span_decode_attn(q, K, V, off, st, en, ctx, np.float32(cfg.scale),
+                                                                 max_tokens=int(tok.max()), num_splits=num_splits))
+            self.dense_calls.append(span.prepare_dense_decode_attn(q, K, V, ctx, np.float32(cfg.scale),
+                                                                   max_tokens=int(sp.ctx_lens.max())))
+            self.span_bytes.append(int(tok.sum()) * row_pair)
+            self.dense_bytes.append(int(sp.ctx_lens.astype(np.int64).sum()) * row_pair)
+            self.coverages.append(sp.coverage())
+            if c == 0:
+                self.host.append((sp, q, K, V))
+        d = self.span_calls[0].desc
+        self.partition = span.span_plan_splits(d)
+
+
+def auto_copies(cfg_id):
+    """Enough copies that the span bytes touched in one rotation are >= 2x the last-level cache."""
+    import numpy as np
+    import paper_2404_09336_amd as span  # noqa: F401
+    from workloads import CONFIGS, draw_spans
+    cfg = CONFIGS[cfg_id]
+    sp = draw_spans(cfg)
+    touched = int(sp.tokens_per_seq().sum()) * 2 * cfg.head_dim * cfg.elt_bytes * cfg.heads
+    alloc = 2 * cfg.batch * cfg.heads * cfg.max_len * cfg.head_dim * cfg.elt_bytes
+    n = int(np.ceil(2 * LLC_BYTES / max(touched, 1)))
+    n = max(1, min(n, 16, max(1, (32 << 30) // alloc)))
+    return n
+
+
+def timed_loop(calls, nbytes, steps, warmup):
+    """Warm up, then time exactly `steps` calls: wall clock bracketed by synchronize, plus HIP events
+    recorded on the launch stream.  Returns dict with per-call times and byte rates."""
+    import torch
+    n = len(calls)
+    for i in range(warmup):
+        calls[i % n]()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    total_bytes = sum(nbytes[i % n] for i in range(steps))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(steps):
+        calls[i % n]()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_s = ev0.elapsed_time(ev1) * 1e-3
+    return {"wall_s": wall, "event_s": ev_s, "bytes_per_call": total_bytes / steps,
+            "us_per_call_wall": wall / steps * 1e6, "us_per_call_event": ev_s / steps * 1e6,
+            "gbps_wall": total_bytes / wall / 1e9, "gbps_event": total_bytes / ev_s / 1e9}
+
+
+def cpu_baseline(wl, budget_s=12.0):
+    """The oracle as it stands on the host cores, on whole batches of the same workload."""
+    import numpy as np
+    import oracle
+    from workloads import to_host_raw
+    sp, q, K, V = wl.host[0]
+    hq, hK, hV = to_host_raw(q), to_host_raw(K), to_host_raw(V)
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        oracle.span_attn(hq, hK, hV, sp.offsets, sp.starts, sp.ends, np.float32(wl.cfg.scale), dtype=wl.cfg.dtype)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or reps >= 1000:
+            break
+    return {"value": wl.span_bytes[0] * reps / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "ms_per_call": dt / reps * 1e3,
+            "sample": f"{reps} whole batch(es) of config {wl.cfg.cfg_id} ({wl.cfg.name}), fp64 two-pass softmax over "
+                      f"span rows, OpenMP over heads"}
+
+
+def read_traffic(cfg_id):
+    """HBM bytes per call measured offline with rocprofv3 --pmc (see profiles/); None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    try:
+        return json.load(open(path)).get(f"config{cfg_id}", {}).get("hbm_bytes_per_call")
+    except (ValueError, OSError):
+        return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one MI355X); --gpus must be 1. The path shards over batch "
+              "or heads with no collective (see DESIGN.md), but no multi-GPU run exists here.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2404_09336_amd as span
+    span.load_library()                      # fail loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    device = torch.device("cuda:0")
+    torch.cuda.set_device(device)
+
+    copies = args.copies or auto_copies(args.config)
+    wl = Workload(args.config, copies, device, coverage=args.coverage, num_splits=args.num_splits)
+    cfg = wl.cfg
+
+    if args.calibrate_copy:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=device)
+        b = torch.zeros(1 << 30, dtype=torch.uint8, device=device)
+        torch.cuda.synchronize()
+        a.copy_(b)
+        torch.cuda.synchronize()
+        del a, b
+
+    res_span = res_dense = res_hot = None
+    if args.only in ("all", "span"):
+        res_span = timed_loop(wl.span_calls, wl.span_bytes, args.steps, args.warmup)
+    if args.only in ("all", "dense"):
+        dsteps = max(10, args.steps // 4) if args.only == "all" else args.steps
+        res_dense = timed_loop(wl.dense_calls, wl.dense_bytes, dsteps, max(5, args.warmup // 4))
+    if args.only == "all":
+        res_hot = timed_loop(wl.span_calls[:1], wl.span_bytes[:1], max(10, args.steps // 4), max(5, args.warmup // 4))
+
+    main_res = res_span or res_dense
+    out = {
+        "metric": "span-KV HBM GB/s" if res_span else "dense-KV HBM GB/s (control)",
+        "value": round(main_res["gbps_wall"], 2), "unit": "GB/s",
+        "pct_of_hbm_peak": round(100.0 * main_res["gbps_wall"] / HBM_PEAK_GBPS, 2),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(main_res["us_per_call_wall"] * 1e-3, 6),
+        "calls_per_s": round(1e6 / main_res["us_per_call_wall"], 1),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype + " inputs, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": f"config {cfg.cfg_id} ({cfg.name}): batch {cfg.batch}, {cfg.heads} heads x "
+                               f"{cfg.head_dim}, KV length {cfg.min_len}-{cfg.max_len}, 1 query token",
+                   "span_coverage": round(sum(wl.coverages) / len(wl.coverages), 4),
+                   "span_bytes_per_call": int(main_res["bytes_per_call"]),
+                   "kv_copies_rotated": copies, "num_splits": wl.partition[0], "slice_tokens": wl.partition[1]},
+        "roofline": {"bound": "hbm", "achieved": round(main_res["gbps_event"], 2), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(main_res["gbps_event"] / HBM_PEAK_GBPS, 4),
+                     "traffic": read_traffic(cfg.cfg_id) if res_span else None,
+                     "us_per_call_hip_events": round(main_res["us_per_call_event"], 3)},
+        "paper_context": PAPER_CONTEXT,
+    }
+    if res_span and res_dense:
+        out["speedup_vs_dense"] = round(res_dense["us_per_call_wall"] / res_span["us_per_call_wall"], 3)
+        out["dense_control"] = {"us_per_call": round(res_dense["us_per_call_wall"], 3),
+                                "gbps": round(res_dense["gbps_wall"], 2),
+                                "pct_of_hbm_peak": round(100.0 * res_dense["gbps_wall"] / HBM_PEAK_GBPS, 2),
+                                "bytes_per_call": int(res_dense["bytes_per_call"])}
+    if res_hot:
+        out["hot_cache_gbps_not_counted"] = round(res_hot["gbps_wall"], 2)
+
+    if args.others:
+        table = {}
+        for cid in (2, 4, 5):
+            del wl
+            torch.cuda.empty_cache()
+            wl = Workload(cid, auto_copies(cid), device)
+            steps = max(20, args.steps // (8 if cid == 5 else 2))
+            s = timed_loop(wl.span_calls, wl.span_bytes, steps, max(5, steps // 10))
+            d = timed_loop(wl.dense_calls, wl.dense_bytes, max(10, steps // 4), 5)
+            table[f"config{cid}"] = {"name": wl.cfg.name, "coverage": round(sum(wl.coverages) / len(wl.coverages), 4),
+                                     "span_gbps": round(s["gbps_wall"], 1),
+                                     "span_pct_peak": round(100 * s["gbps_wall"] / HBM_PEAK_GBPS, 2),
+                                     "span_us": round(s["us_per_call_wall"], 2),
+                                     "dense_us": round(d["us_per_call_wall"], 2),
+                                     "dense_gbps": round(d["gbps_wall"], 1),
+                                     "speedup_vs_dense": round(d["us_per_call_wall"] / s["us_per_call_wall"], 3),
+                                     "splits": wl.partition[0]}
+        out["workloads"] = table
+        del wl
+        torch.cuda.empty_cache()
+        wl = Workload(args.config, 1, device)
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -148,9 +148,22 @@ def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, wo
     return desc, out, workspace
 
 
-def span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out=None, *,
-                     max_tokens=0, num_splits=0, workspace=None, stream=None):
-    """out[b,h,:] = softmax over the span's positions of scale*q.K, times V.  Returns `out` (fp32)."""
+class PreparedCall:
+    """One fully marshalled call: holds the descriptor, raw pointers and the tensors they point into, so
+    that invoking it costs a single ctypes call (used by tight loops such as the benchmark)."""
+
+    def __init__(self, name, fn, desc, args, out, keepalive):
+        self.name, self._fn, self.desc, self._args, self.out, self._keepalive = name, fn, desc, args, out, keepalive
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != 0:
+            raise SpanAttnError(rc, self.name)
+        return self.out
+
+
+def prepare_span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out=None, *,
+                             max_tokens=0, num_splits=0, workspace=None, stream=None) -> PreparedCall:
     lib = load_library()
     n_int = int(span_starts.numel())
     desc, out, workspace = _prepare(q, k_cache, v_cache, out, n_int, max_tokens, num_splits, workspace, stream)
@@ -158,21 +171,33 @@ def span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, 
     st_p = _i32_dev(span_starts, n_int, "span_starts")
     en_p = _i32_dev(span_ends, n_int, "span_ends")
     ctx_p = _i32_dev(ctx_lens, desc.batch, "ctx_lens") if ctx_lens is not None else None
-    rc = lib.span_decode_attn(ctypes.byref(desc), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), off_p, st_p,
-                              en_p, ctx_p, float(scale), out.data_ptr())
-    if rc != 0:
-        raise SpanAttnError(rc, "span_decode_attn")
-    return out
+    args = (ctypes.byref(desc), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), off_p, st_p, en_p, ctx_p,
+            float(scale), out.data_ptr())
+    keep = (q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, workspace)
+    return PreparedCall("span_decode_attn", lib.span_decode_attn, desc, args, out, keep)
+
+
+def prepare_dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out=None, *, max_tokens=0, num_splits=0,
+                              workspace=None, stream=None) -> PreparedCall:
+    lib = load_library()
+    desc, out, workspace = _prepare(q, k_cache, v_cache, out, 0, max_tokens, num_splits, workspace, stream)
+    ctx_p = _i32_dev(ctx_lens, desc.batch, "ctx_lens")
+    args = (ctypes.byref(desc), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), ctx_p, float(scale),
+            out.data_ptr())
+    return PreparedCall("dense_decode_attn", lib.dense_decode_attn, desc, args, out,
+                        (q, k_cache, v_cache, ctx_lens, workspace))
+
+
+def span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out=None, *,
+                     max_tokens=0, num_splits=0, workspace=None, stream=None):
+    """out[b,h,:] = softmax over the span's positions of scale*q.K, times V.  Returns `out` (fp32)."""
+    return prepare_span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out,
+                                    max_tokens=max_tokens, num_splits=num_splits, workspace=workspace,
+                                    stream=stream)()
 
 
 def dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out=None, *, max_tokens=0, num_splits=0,
                       workspace=None, stream=None):
     """Dense control: every position below ctx_lens[b] is attended."""
-    lib = load_library()
-    desc, out, workspace = _prepare(q, k_cache, v_cache, out, 0, max_tokens, num_splits, workspace, stream)
-    ctx_p = _i32_dev(ctx_lens, desc.batch, "ctx_lens")
-    rc = lib.dense_decode_attn(ctypes.byref(desc), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), ctx_p,
-                               float(scale), out.data_ptr())
-    if rc != 0:
-        raise SpanAttnError(rc, "dense_decode_attn")
-    return out
+    return prepare_dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out, max_tokens=max_tokens,
+                                     num_splits=num_splits, workspace=workspace, stream=stream)()

@@ -65,7 +65,10 @@ typedef struct span_attn_desc {
                               per (batch, head) (the library may raise it, see
                               span_plan_splits)                                                  */
   void* workspace;         /* device, 256-byte aligned, >= span_workspace_bytes(); may be NULL
-                              when that is 0                                                     */
+                              when that is 0.  Its leading ticket counters must be zero before the
+                              first call that uses it (span_workspace_init, or zero the buffer);
+                              every call leaves them zero again.  Two calls that may overlap in
+                              time must not share a workspace.                                  */
   size_t workspace_bytes;
   void* stream;            /* hipStream_t; NULL = the default stream                             */
 } span_attn_desc_t;
@@ -124,12 +127,20 @@ int span_validate(int32_t batch, int32_t num_intervals, const int32_t* span_offs
  * How the library would partition the call described by desc: the number of KV slices per
  * (batch, head) and the number of attended positions each slice owns.  One slice means the
  * kernel writes `out` directly; more than one means partial softmax states go through the
- * workspace and a second kernel merges them by log-sum-exp.  Pure host arithmetic.
+ * workspace and, per (batch, head), the workgroup that finishes last merges them by log-sum-exp
+ * (still one launch).  Pure host arithmetic.
  */
 int span_plan_splits(const span_attn_desc_t* desc, int32_t* num_splits, int32_t* slice_tokens);
 
 /* Bytes of device workspace the call described by desc needs (0 when one slice is used). */
 size_t span_workspace_bytes(const span_attn_desc_t* desc);
+
+/*
+ * Enqueues, on desc->stream, the zeroing of the ticket counters at the head of desc->workspace.
+ * Needed once after the workspace is allocated (or after anything else wrote to it), not per call.
+ * Uses hipMemsetAsync: do not call it while the stream is being captured into a HIP graph.
+ */
+int span_workspace_init(const span_attn_desc_t* desc);
 
 /* Static string for any code above. */
 const char* span_strerror(int code);

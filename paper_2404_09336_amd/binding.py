@@ -53,6 +53,8 @@ def load_library():
         lib.span_plan_splits.restype = ctypes.c_int
         lib.span_workspace_bytes.argtypes = [DP]
         lib.span_workspace_bytes.restype = ctypes.c_size_t
+        lib.span_workspace_init.argtypes = [DP]
+        lib.span_workspace_init.restype = ctypes.c_int
         lib.span_strerror.argtypes = [ctypes.c_int]
         lib.span_strerror.restype = ctypes.c_char_p
         lib.span_last_hip_error.restype = ctypes.c_int
@@ -89,6 +91,13 @@ def span_plan_splits(desc: _Desc):
 
 def span_workspace_bytes(desc: _Desc) -> int:
     return int(load_library().span_workspace_bytes(ctypes.byref(desc)))
+
+
+def span_workspace_init(desc: _Desc) -> None:
+    """Zeroes the ticket counters at the head of desc.workspace (enqueued on desc.stream)."""
+    rc = load_library().span_workspace_init(ctypes.byref(desc))
+    if rc != 0:
+        raise SpanAttnError(rc, "span_workspace_init")
 
 
 def span_validate(span_offsets, span_starts, span_ends, ctx_lens):
@@ -141,10 +150,13 @@ def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, wo
     desc = make_desc(B, H, D, L, _dtype_code(q), num_intervals, int(max_tokens), int(num_splits), 0, 0, stream)
     need = span_workspace_bytes(desc)
     if need:
-        if workspace is None:
+        fresh = workspace is None
+        if fresh:
             workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
         desc.workspace = workspace.data_ptr()
         desc.workspace_bytes = workspace.numel() * workspace.element_size()
+        if fresh:
+            span_workspace_init(desc)   # a workspace handed in by the caller must already be initialised
     return desc, out, workspace
 
 

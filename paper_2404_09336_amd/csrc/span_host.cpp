@@ -50,7 +50,7 @@ int check_desc(const span_attn_desc_t* d) {
   if (d->head_dim != 64 && d->head_dim != 128) return SPAN_ERR_SHAPE;
   if (d->num_intervals < 0 || d->max_tokens < 0 || d->num_splits < 0) return SPAN_ERR_SHAPE;
   if ((int64_t)d->batch * d->heads > INT_MAX / 2) return SPAN_ERR_SHAPE;
-  if (d->heads > 65535 || d->batch > 65535) return SPAN_ERR_SHAPE;  // grid y / z limits
+  if (d->batch > 65535) return SPAN_ERR_SHAPE;  // grid z limit
   if (d->dtype != SPAN_F32 && d->dtype != SPAN_F16 && d->dtype != SPAN_BF16) return SPAN_ERR_DTYPE;
   return SPAN_OK;
 }
@@ -70,12 +70,18 @@ Partition plan_partition(const span_attn_desc_t* d) {
   if (splits < 1) splits = 1;
   int64_t slice = ceil_div(ceil_div(max_tok, splits), kSliceGranule) * kSliceGranule;
   if (slice > kMaxSlice) slice = kMaxSlice;
+  while (ceil_div(max_tok, slice) > 65535) slice += kSliceGranule;  // grid.y limit
   splits = ceil_div(max_tok, slice);
   Partition p;
   p.num_splits = (int32_t)splits;
   p.slice_tokens = (int32_t)slice;
   p.max_tokens = (int32_t)max_tok;
   return p;
+}
+
+size_t workspace_counter_bytes(const span_attn_desc_t* d) {
+  const size_t n = (size_t)d->batch * d->heads * sizeof(int32_t);
+  return (n + 255) & ~(size_t)255;
 }
 
 size_t workspace_ml_bytes(const span_attn_desc_t* d, const Partition& p) {
@@ -85,7 +91,7 @@ size_t workspace_ml_bytes(const span_attn_desc_t* d, const Partition& p) {
 
 size_t workspace_bytes(const span_attn_desc_t* d, const Partition& p) {
   if (p.num_splits <= 1) return 0;
-  return workspace_ml_bytes(d, p) + (size_t)d->batch * d->heads * p.num_splits * d->head_dim * sizeof(float);
+  return workspace_counter_bytes(d) + workspace_ml_bytes(d, p) + (size_t)d->batch * d->heads * p.num_splits * d->head_dim * sizeof(float);
 }
 
 }  // namespace spanattn

@@ -24,6 +24,7 @@ struct Partition {
 
 int check_desc(const span_attn_desc_t* d);
 Partition plan_partition(const span_attn_desc_t* d);
+size_t workspace_counter_bytes(const span_attn_desc_t* d);
 size_t workspace_ml_bytes(const span_attn_desc_t* d, const Partition& p);
 size_t workspace_bytes(const span_attn_desc_t* d, const Partition& p);
 

@@ -8,7 +8,7 @@
 //
 // Mapping to the machine (single-query decode is a GEMV: one multiply-add per loaded element, so
 // the kernel is bound by HBM and uses no matrix cores):
-//   * grid = (KV slices, heads, batch).  A sequence's span is flattened into a virtual token index
+//   * grid = (heads, KV slices, batch).  A sequence's span is flattened into a virtual token index
 //     0..n_b-1 (prefix sums of the interval lengths); slice s owns virtual tokens [s*T, (s+1)*T).
 //     The host picks T so that short spans still give every CU several workgroups.
 //   * a workgroup is 4 wavefronts; each wavefront takes a contiguous quarter of the slice and is
@@ -18,7 +18,9 @@
 //     lane a 128-bit piece.  The q.k dot product is finished with DPP adds inside those lanes; every
 //     row group of a wavefront carries its own online-softmax state (m, l, acc), merged by
 //     log-sum-exp at the end: first across row groups (shuffles), then across wavefronts (LDS), then
-//     - only if the call uses more than one slice - across slices by a second small kernel.
+//     - only if the call uses more than one slice - across slices: every workgroup publishes its
+//     state and takes a ticket; the one that arrives last for its (batch, head) merges them all, so
+//     the whole call is a single launch.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -44,6 +46,7 @@ struct LaunchArgs {
   const int32_t* starts;
   const int32_t* ends;
   const int32_t* ctx_lens;
+  int32_t* counters;  // [batch*heads] arrival tickets of the slices; zero between calls
   float* part_ml;   // [batch*heads, num_splits, 2]  (m in log2 units, l)
   float* part_acc;  // [batch*heads, num_splits, D]  un-normalised
   int32_t heads, max_len, num_intervals, slice_tokens, num_splits, max_tokens;
@@ -126,6 +129,14 @@ __device__ __forceinline__ u32x4 load_row_piece(const char* slab, uint32_t byte_
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(slab + byte_off));
 }
 
+// Device-coherent store / load of one float that another workgroup reads / wrote in the same kernel.
+__device__ __forceinline__ void publish(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float observe(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Merge two un-normalised softmax states held in log2 units.
 __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int n, float m2, float l2,
                                             const float* acc2) {
@@ -139,14 +150,16 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int 
 
 // ---- the streaming kernel ------------------------------------------------------------------------
 template <class Elt, int D, bool kDense, int U>
-__global__ __launch_bounds__(kThreads) void partial_kernel(const LaunchArgs a) {
+__global__ __launch_bounds__(kThreads) void decode_kernel(const LaunchArgs a) {
   constexpr int EPL = Elt::kPerVec;        // elements per lane (one 128-bit piece)
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPL = 64 / LPR;            // rows per wave-wide load
   constexpr uint32_t ROWB = D * Elt::kBytes;
   static_assert(LPR == 8 || LPR == 16 || LPR == 32, "row must span 8, 16 or 32 lanes");
 
-  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  // heads vary fastest: consecutive workgroups go to different XCDs, and the 'is this slice empty'
+  // answer is the same for all heads of a (batch, slice), so full and empty slices spread evenly
+  const int h = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int grp = lane / LPR, lir = lane % LPR;
   const size_t bh = (size_t)b * a.heads + h;
@@ -156,6 +169,8 @@ __global__ __launch_bounds__(kThreads) void partial_kernel(const LaunchArgs a) {
   __shared__ int s_start[kWavesPerBlock][64];
   __shared__ float s_acc[kWavesPerBlock][D];
   __shared__ float s_ml[kWavesPerBlock][2];
+  __shared__ float s_gm[kWavesPerBlock][D], s_gl[kWavesPerBlock][D];
+  __shared__ int s_ticket;
 
   // q piece of this lane, pre-multiplied by scale*log2(e) so that exp() becomes exp2().
   float qf[EPL];
@@ -194,17 +209,9 @@ __global__ __launch_bounds__(kThreads) void partial_kernel(const LaunchArgs a) {
   n_total = n_total < a.max_tokens ? n_total : a.max_tokens;
   const int cnt = __builtin_amdgcn_readfirstlane(clampi(n_total - slice_begin, 0, T));
 
-  if (cnt == 0) {  // nothing of this sequence falls into the slice (same decision in all 4 waves)
-    if (a.num_splits == 1) {
-      if (tid < D) a.out[bh * D + tid] = 0.f;
-    } else if (tid == 0) {
-      float* ml = a.part_ml + (bh * a.num_splits + split) * 2;
-      ml[0] = -INFINITY;
-      ml[1] = 0.f;
-    }
-    return;
-  }
-
+  // State of this slice for output column tid (tid < D): un-normalised, m in log2 units.
+  float M = -INFINITY, L = 0.f, o = 0.f;
+  if (cnt > 0) {  // same decision in all 4 waves
   // rows of the slice are dealt to the 4 waves in contiguous, RPL-aligned shares
   const int rpw = (((cnt + kWavesPerBlock - 1) / kWavesPerBlock) + RPL - 1) / RPL * RPL;
   const int wb = min(wave * rpw, cnt);
@@ -331,60 +338,80 @@ __global__ __launch_bounds__(kThreads) void partial_kernel(const LaunchArgs a) {
   }
   __syncthreads();
   if (tid < D) {
-    float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kWavesPerBlock; ++w)
       if (s_ml[w][1] > 0.f) M = fmaxf(M, s_ml[w][0]);
-    float L = 0.f, o = 0.f;
 #pragma unroll
     for (int w = 0; w < kWavesPerBlock; ++w) {
       const float wgt = s_ml[w][1] > 0.f ? __builtin_amdgcn_exp2f(s_ml[w][0] - M) : 0.f;
       L += wgt * s_ml[w][1];
       o += wgt * s_acc[w][tid];
     }
-    if (a.num_splits == 1) {
-      a.out[bh * D + tid] = L > 0.f ? o / L : 0.f;
-    } else {
-      const size_t slot = bh * a.num_splits + split;
-      a.part_acc[slot * D + tid] = o;
-      if (tid == 0) {
-        a.part_ml[slot * 2] = M;
-        a.part_ml[slot * 2 + 1] = L;
-      }
-    }
   }
-}
+  }  // cnt > 0
 
-// ---- merge of the slices' states (only when num_splits > 1) --------------------------------------
-template <int D>
-__global__ __launch_bounds__(D) void merge_kernel(const LaunchArgs a) {
-  const size_t bh = (size_t)blockIdx.y * a.heads + blockIdx.x;
-  const int t = threadIdx.x;
-  const float* ml = a.part_ml + bh * a.num_splits * 2;
-  const float* pa = a.part_acc + bh * a.num_splits * D;
-  float M = -INFINITY;
-  for (int s = 0; s < a.num_splits; ++s)
-    if (ml[2 * s + 1] > 0.f) M = fmaxf(M, ml[2 * s]);
-  float L = 0.f, o = 0.f;
-  for (int s = 0; s < a.num_splits; ++s) {
-    const float ls = ml[2 * s + 1];
-    if (ls > 0.f) {
-      const float w = __builtin_amdgcn_exp2f(ml[2 * s] - M);
-      L += w * ls;
-      o += w * pa[(size_t)s * D + t];
-    }
+  if (a.num_splits == 1) {  // one slice per (batch, head): this workgroup owns the output row
+    if (tid < D) a.out[bh * D + tid] = L > 0.f ? o / L : 0.f;
+    return;
   }
-  a.out[bh * D + t] = L > 0.f ? o / L : 0.f;
+
+  // ---- step 5: several slices.  Publish this slice's state; the workgroup that arrives last for
+  // (b, h) merges all of them by log-sum-exp and writes the output row (no second kernel launch).
+  //
+  // Cross-workgroup hand-over without cache-wide fences: the states are written and read with
+  // device-scope relaxed atomics (write-through / cache-bypassing accesses, each coherent on its own),
+  // the writer waits for its stores to be acknowledged before the ticket is taken, and the reader
+  // only starts after its own ticket came back.  A device-scope fence would write back and
+  // invalidate the whole L2 of the XCD for every workgroup, which costs far more than the merge.
+  const size_t slot0 = bh * a.num_splits;
+  if (tid < D) {
+    if (cnt > 0) publish(&a.part_acc[(slot0 + split) * D + tid], o);
+    if (tid == 0) {
+      publish(&a.part_ml[(slot0 + split) * 2], M);
+      publish(&a.part_ml[(slot0 + split) * 2 + 1], L);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my published stores are acknowledged
+  }
+  __syncthreads();
+  if (tid == 0) s_ticket = __hip_atomic_fetch_add(&a.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (s_ticket != a.num_splits - 1) return;
+
+  constexpr int G = kThreads / D;  // column t is merged by G threads, each over every G-th slice
+  const int g = tid / D, t = tid % D;
+  const float* ml = a.part_ml + slot0 * 2;
+  const float* pa = a.part_acc + slot0 * D;
+  float mm = -INFINITY, ll = 0.f, oo = 0.f;
+#pragma unroll 4
+  for (int s = g; s < a.num_splits; s += G) {
+    const float ms = observe(&ml[2 * s]), ls = observe(&ml[2 * s + 1]);
+    float as = observe(&pa[(size_t)s * D + t]);  // slot of an empty slice is never written: select, do not scale
+    as = ls > 0.f ? as : 0.f;
+    merge_state(mm, ll, &oo, 1, ls > 0.f ? ms : -INFINITY, ls > 0.f ? ls : 0.f, &as);
+  }
+  if (g > 0) {
+    s_acc[g][t] = oo;
+    s_gm[g][t] = mm;
+    s_gl[g][t] = ll;
+  }
+  __syncthreads();
+  if (g == 0) {
+#pragma unroll
+    for (int j = 1; j < G; ++j) {
+      const float o2 = s_acc[j][t];
+      merge_state(mm, ll, &oo, 1, s_gm[j][t], s_gl[j][t], &o2);
+    }
+    a.out[bh * D + t] = ll > 0.f ? oo / ll : 0.f;
+    if (tid == 0) a.counters[bh] = 0;  // leave the ticket counter ready for the next call
+  }
 }
 
 thread_local int g_last_hip_error = 0;
 
 template <class Elt, int D, bool kDense>
 int launch_typed(const LaunchArgs& a, int batch, hipStream_t stream) {
-  const dim3 grid((unsigned)a.num_splits, (unsigned)a.heads, (unsigned)batch);
-  hipLaunchKernelGGL((partial_kernel<Elt, D, kDense, 4>), grid, dim3(kThreads), 0, stream, a);
-  if (a.num_splits > 1)
-    hipLaunchKernelGGL((merge_kernel<D>), dim3((unsigned)a.heads, (unsigned)batch), dim3(D), 0, stream, a);
+  const dim3 grid((unsigned)a.heads, (unsigned)a.num_splits, (unsigned)batch);
+  hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, 4>), grid, dim3(kThreads), 0, stream, a);
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) {
     g_last_hip_error = (int)err;
@@ -414,8 +441,9 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   a.starts = starts;
   a.ends = ends;
   a.ctx_lens = ctx_lens;
-  a.part_ml = need ? (float*)d->workspace : nullptr;
-  a.part_acc = need ? (float*)((char*)d->workspace + workspace_ml_bytes(d, p)) : nullptr;
+  a.counters = need ? (int32_t*)d->workspace : nullptr;
+  a.part_ml = need ? (float*)((char*)d->workspace + workspace_counter_bytes(d)) : nullptr;
+  a.part_acc = need ? (float*)((char*)d->workspace + workspace_counter_bytes(d) + workspace_ml_bytes(d, p)) : nullptr;
   a.heads = d->heads;
   a.max_len = d->max_len;
   a.num_intervals = d->num_intervals;
@@ -449,6 +477,22 @@ extern "C" int span_decode_attn(const span_attn_desc_t* desc, const void* q, con
 extern "C" int dense_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_cache,
                                  const void* v_cache, const int32_t* ctx_lens, float scale, float* out) {
   return spanattn::launch<true>(desc, q, k_cache, v_cache, nullptr, nullptr, nullptr, ctx_lens, scale, out);
+}
+
+extern "C" int span_workspace_init(const span_attn_desc_t* desc) {
+  const int rc = spanattn::check_desc(desc);
+  if (rc != SPAN_OK) return rc;
+  const spanattn::Partition p = spanattn::plan_partition(desc);
+  const size_t need = spanattn::workspace_bytes(desc, p);
+  if (need == 0) return SPAN_OK;
+  if (!desc->workspace || ((uintptr_t)desc->workspace & 255u) || desc->workspace_bytes < need) return SPAN_ERR_WORKSPACE;
+  const hipError_t err =
+      hipMemsetAsync(desc->workspace, 0, spanattn::workspace_counter_bytes(desc), (hipStream_t)desc->stream);
+  if (err != hipSuccess) {
+    spanattn::g_last_hip_error = (int)err;
+    return SPAN_ERR_HIP;
+  }
+  return SPAN_OK;
 }
 
 extern "C" int span_last_hip_error(void) { return spanattn::g_last_hip_error; }

@@ -132,8 +132,15 @@ def test_caller_workspace_is_used_and_sufficient(gpu_device):
     d = binding.make_desc(2, 2, 128, 512, 1, 2, 0, 4)
     need = span.span_workspace_bytes(d)
     ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=gpu_device)   # NaN bit patterns everywhere
+    d.workspace, d.workspace_bytes = ws.data_ptr(), need
+    d.stream = torch.cuda.current_stream(gpu_device).cuda_stream
+    span.span_workspace_init(d)                                            # zeroes only the ticket counters
     got = run_span(cfg, sp, q, K, V, gpu_device, num_splits=4, max_tokens=0, workspace=ws)
-    check(got, oracle_span(cfg, sp, q, K, V), cfg.tol, "caller workspace pre-filled with 0xFF")
+    ref = oracle_span(cfg, sp, q, K, V)
+    check(got, ref, cfg.tol, "caller workspace pre-filled with 0xFF")
+    for i in range(3):   # the call leaves the counters zero: the same workspace serves the next calls
+        got = run_span(cfg, sp, q, K, V, gpu_device, num_splits=4, max_tokens=0, workspace=ws)
+        check(got, ref, cfg.tol, f"workspace reused, call {i + 2}")
 
 
 # ------------------------------------------------------------------ degenerate and edge cases

@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--copies", type=int, default=0, help="independent KV copies to rotate over (0 = auto)")
     ap.add_argument("--coverage", type=float, default=None, help="config 5 only: uniform span coverage")
     ap.add_argument("--num-splits", type=int, default=0)
+    ap.add_argument("--uniform-grid", action="store_true",
+                    help="do not pass per-sequence token counts (every sequence gets the same number of slices)")
     ap.add_argument("--only", choices=["all", "span", "dense"], default="all",
                     help="'span' / 'dense' run just that timed loop (for profiling one kernel)")
     ap.add_argument("--others", action="store_true", help="also time configs 2, 4, 5 (reported under 'workloads')")
@@ -49,7 +51,7 @@ def parse_args():
 class Workload:
     """`copies` independent instances of one config: tensors on the GPU plus prepared calls."""
 
-    def __init__(self, cfg_id, copies, device, coverage=None, num_splits=0):
+    def __init__(self, cfg_id, copies, device, coverage=None, num_splits=0, exact=True):
         import numpy as np
         import torch
         import paper_2404_09336_amd as span
@@ -67,16 +69,18 @@ class Workload:
             dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
             off, st, en, ctx = dev(sp.offsets), dev(sp.starts), dev(sp.ends), dev(sp.ctx_lens)
             self.span_calls.append(span.prepare_span_decode_attn(q, K, V, off, st, en, ctx, np.float32(cfg.scale),
-                                                                 max_tokens=int(tok.max()), num_splits=num_splits))
-            self.dense_calls.append(span.prepare_dense_decode_attn(q, K, V, ctx, np.float32(cfg.scale),
-                                                                   max_tokens=int(sp.ctx_lens.max())))
+                                                                 max_tokens=int(tok.max()), num_splits=num_splits,
+                                                                 tokens_per_seq=tok if exact else None))
+            self.dense_calls.append(span.prepare_dense_decode_attn(
+                q, K, V, ctx, np.float32(cfg.scale), max_tokens=int(sp.ctx_lens.max()),
+                tokens_per_seq=sp.ctx_lens.astype(np.int64) if exact else None))
             self.span_bytes.append(int(tok.sum()) * row_pair)
             self.dense_bytes.append(int(sp.ctx_lens.astype(np.int64).sum()) * row_pair)
             self.coverages.append(sp.coverage())
             if c == 0:
                 self.host.append((sp, q, K, V))
-        d = self.span_calls[0].desc
-        self.partition = span.span_plan_splits(d)
+        self.plan = span.span_plan_query(self.span_calls[0].desc)
+        self.partition = (self.plan["max_splits"], self.plan["slice_tokens"], self.plan["workgroups"])
 
 
 def auto_copies(cfg_id):
@@ -163,7 +167,8 @@ def main():
     torch.cuda.set_device(device)
 
     copies = args.copies or auto_copies(args.config)
-    wl = Workload(args.config, copies, device, coverage=args.coverage, num_splits=args.num_splits)
+    wl = Workload(args.config, copies, device, coverage=args.coverage, num_splits=args.num_splits,
+                  exact=not args.uniform_grid)
     cfg = wl.cfg
 
     if args.calibrate_copy:
@@ -197,7 +202,7 @@ def main():
                                f"{cfg.head_dim}, KV length {cfg.min_len}-{cfg.max_len}, 1 query token",
                    "span_coverage": round(sum(wl.coverages) / len(wl.coverages), 4),
                    "span_bytes_per_call": int(main_res["bytes_per_call"]),
-                   "kv_copies_rotated": copies, "num_splits": wl.partition[0], "slice_tokens": wl.partition[1]},
+                   "kv_copies_rotated": copies, "plan": wl.plan},
         "roofline": {"bound": "hbm", "achieved": round(main_res["gbps_event"], 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(main_res["gbps_event"] / HBM_PEAK_GBPS, 4),
                      "traffic": read_traffic(cfg.cfg_id) if res_span else None,

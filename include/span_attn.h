@@ -64,6 +64,13 @@ typedef struct span_attn_desc {
   int32_t num_splits;      /* 0 = let the library choose; > 0 = requested number of KV slices
                               per (batch, head) (the library may raise it, see
                               span_plan_splits)                                                  */
+  const int64_t* tokens_per_seq; /* HOST int64 [batch] or NULL: attended positions of every sequence, as
+                              span_validate returns them (for the dense call: ctx_lens widened).
+                              Lets the library cut the batch into equal-sized slices with no idle
+                              workgroup (ragged batches).  Read during the call only.  If it
+                              understates a sequence, that sequence's excess positions may be
+                              dropped; memory safety does not depend on it.  Ignored when
+                              num_splits > 0 or batch > 1024.                                    */
   void* workspace;         /* device, 256-byte aligned, >= span_workspace_bytes(); may be NULL
                               when that is 0.  Its leading ticket counters must be zero before the
                               first call that uses it (span_workspace_init, or zero the buffer);
@@ -124,13 +131,21 @@ int span_validate(int32_t batch, int32_t num_intervals, const int32_t* span_offs
                   int32_t* first_bad_interval, int64_t* span_tokens_per_seq);
 
 /*
- * How the library would partition the call described by desc: the number of KV slices per
- * (batch, head) and the number of attended positions each slice owns.  One slice means the
- * kernel writes `out` directly; more than one means partial softmax states go through the
- * workspace and, per (batch, head), the workgroup that finishes last merges them by log-sum-exp
- * (still one launch).  Pure host arithmetic.
+ * How the library would partition the call described by desc.  A (batch, head) pair whose span is
+ * cut into one slice has its output row written directly; with more slices the partial softmax
+ * states go through the workspace and the workgroup that finishes last for the pair merges them by
+ * log-sum-exp (still one launch).  Pure host arithmetic.
  */
-int span_plan_splits(const span_attn_desc_t* desc, int32_t* num_splits, int32_t* slice_tokens);
+typedef struct span_plan_info {
+  int32_t exact;           /* 1: slices sized from tokens_per_seq (no idle workgroup); 0: every
+                              sequence gets max_splits slices of slice_tokens positions            */
+  int32_t slice_tokens;    /* attended positions per slice (upper bound in exact mode)            */
+  int32_t max_splits;      /* most slices any (batch, head) pair is cut into                      */
+  int32_t reserved;
+  int64_t workgroups;      /* workgroups the call launches                                        */
+  int64_t workspace_bytes; /* same value as span_workspace_bytes()                                */
+} span_plan_info_t;
+int span_plan_query(const span_attn_desc_t* desc, span_plan_info_t* info);
 
 /* Bytes of device workspace the call described by desc needs (0 when one slice is used). */
 size_t span_workspace_bytes(const span_attn_desc_t* desc);

@@ -25,8 +25,17 @@ class _Desc(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("max_len", ctypes.c_int32), ("dtype", ctypes.c_int32), ("num_intervals", ctypes.c_int32),
                 ("max_tokens", ctypes.c_int32), ("num_splits", ctypes.c_int32),
-                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("tokens_per_seq", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p)]
+
+
+class PlanInfo(ctypes.Structure):
+    _fields_ = [("exact", ctypes.c_int32), ("slice_tokens", ctypes.c_int32), ("max_splits", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("workgroups", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
+
+    def as_dict(self):
+        return {"exact": bool(self.exact), "slice_tokens": self.slice_tokens, "max_splits": self.max_splits,
+                "workgroups": self.workgroups, "workspace_bytes": self.workspace_bytes}
 
 
 def lib_path() -> str:
@@ -49,8 +58,8 @@ def load_library():
         lib.dense_decode_attn.restype = ctypes.c_int
         lib.span_validate.argtypes = [I32, I32, P, P, P, P, P, P, P]
         lib.span_validate.restype = ctypes.c_int
-        lib.span_plan_splits.argtypes = [DP, P, P]
-        lib.span_plan_splits.restype = ctypes.c_int
+        lib.span_plan_query.argtypes = [DP, ctypes.POINTER(PlanInfo)]
+        lib.span_plan_query.restype = ctypes.c_int
         lib.span_workspace_bytes.argtypes = [DP]
         lib.span_workspace_bytes.restype = ctypes.c_size_t
         lib.span_workspace_init.argtypes = [DP]
@@ -75,18 +84,25 @@ def _dtype_code(t):
 
 
 def make_desc(batch, heads, head_dim, max_len, dtype_code, num_intervals=0, max_tokens=0, num_splits=0,
-              workspace_ptr=0, workspace_bytes=0, stream=0) -> _Desc:
-    return _Desc(batch, heads, head_dim, max_len, dtype_code, num_intervals, max_tokens, num_splits,
-                 workspace_ptr or None, workspace_bytes, stream or None)
+              workspace_ptr=0, workspace_bytes=0, stream=0, tokens_per_seq=None) -> _Desc:
+    """tokens_per_seq: host int64 numpy array [batch] or None; the descriptor keeps a reference to it."""
+    d = _Desc(batch, heads, head_dim, max_len, dtype_code, num_intervals, max_tokens, num_splits, None,
+              workspace_ptr or None, workspace_bytes, stream or None)
+    if tokens_per_seq is not None:
+        tok = np.ascontiguousarray(tokens_per_seq, dtype=np.int64).reshape(-1)
+        if tok.shape[0] != batch:
+            raise ValueError("tokens_per_seq must have one entry per sequence")
+        d._tokens_keepalive = tok
+        d.tokens_per_seq = tok.ctypes.data
+    return d
 
 
-def span_plan_splits(desc: _Desc):
-    ns, st = ctypes.c_int32(), ctypes.c_int32()
-    rc = load_library().span_plan_splits(ctypes.byref(desc), ctypes.cast(ctypes.byref(ns), ctypes.c_void_p),
-                                         ctypes.cast(ctypes.byref(st), ctypes.c_void_p))
+def span_plan_query(desc: _Desc) -> dict:
+    info = PlanInfo()
+    rc = load_library().span_plan_query(ctypes.byref(desc), ctypes.byref(info))
     if rc != 0:
-        raise SpanAttnError(rc, "span_plan_splits")
-    return ns.value, st.value
+        raise SpanAttnError(rc, "span_plan_query")
+    return info.as_dict()
 
 
 def span_workspace_bytes(desc: _Desc) -> int:
@@ -138,7 +154,7 @@ def _i32_dev(t, n, name):
     return t.data_ptr()
 
 
-def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, workspace, stream):
+def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, workspace, stream, tokens_per_seq):
     import torch
     B, H, L, D = _check_qkv(q, k_cache, v_cache)
     if out is None:
@@ -147,7 +163,8 @@ def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, wo
         raise ValueError("out must be a contiguous fp32 GPU tensor [B,H,D]")
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
-    desc = make_desc(B, H, D, L, _dtype_code(q), num_intervals, int(max_tokens), int(num_splits), 0, 0, stream)
+    desc = make_desc(B, H, D, L, _dtype_code(q), num_intervals, int(max_tokens), int(num_splits), 0, 0, stream,
+                     tokens_per_seq)
     need = span_workspace_bytes(desc)
     if need:
         fresh = workspace is None
@@ -175,10 +192,12 @@ class PreparedCall:
 
 
 def prepare_span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out=None, *,
-                             max_tokens=0, num_splits=0, workspace=None, stream=None) -> PreparedCall:
+                             max_tokens=0, num_splits=0, workspace=None, stream=None,
+                             tokens_per_seq=None) -> PreparedCall:
     lib = load_library()
     n_int = int(span_starts.numel())
-    desc, out, workspace = _prepare(q, k_cache, v_cache, out, n_int, max_tokens, num_splits, workspace, stream)
+    desc, out, workspace = _prepare(q, k_cache, v_cache, out, n_int, max_tokens, num_splits, workspace, stream,
+                                    tokens_per_seq)
     off_p = _i32_dev(span_offsets, desc.batch + 1, "span_offsets")
     st_p = _i32_dev(span_starts, n_int, "span_starts")
     en_p = _i32_dev(span_ends, n_int, "span_ends")
@@ -190,9 +209,10 @@ def prepare_span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, spa
 
 
 def prepare_dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out=None, *, max_tokens=0, num_splits=0,
-                              workspace=None, stream=None) -> PreparedCall:
+                              workspace=None, stream=None, tokens_per_seq=None) -> PreparedCall:
     lib = load_library()
-    desc, out, workspace = _prepare(q, k_cache, v_cache, out, 0, max_tokens, num_splits, workspace, stream)
+    desc, out, workspace = _prepare(q, k_cache, v_cache, out, 0, max_tokens, num_splits, workspace, stream,
+                                    tokens_per_seq)
     ctx_p = _i32_dev(ctx_lens, desc.batch, "ctx_lens")
     args = (ctypes.byref(desc), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), ctx_p, float(scale),
             out.data_ptr())
@@ -201,15 +221,16 @@ def prepare_dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out=None, *,
 
 
 def span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out=None, *,
-                     max_tokens=0, num_splits=0, workspace=None, stream=None):
+                     max_tokens=0, num_splits=0, workspace=None, stream=None, tokens_per_seq=None):
     """out[b,h,:] = softmax over the span's positions of scale*q.K, times V.  Returns `out` (fp32)."""
     return prepare_span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out,
                                     max_tokens=max_tokens, num_splits=num_splits, workspace=workspace,
-                                    stream=stream)()
+                                    stream=stream, tokens_per_seq=tokens_per_seq)()
 
 
 def dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out=None, *, max_tokens=0, num_splits=0,
-                      workspace=None, stream=None):
+                      workspace=None, stream=None, tokens_per_seq=None):
     """Dense control: every position below ctx_lens[b] is attended."""
     return prepare_dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out, max_tokens=max_tokens,
-                                     num_splits=num_splits, workspace=workspace, stream=stream)()
+                                     num_splits=num_splits, workspace=workspace, stream=stream,
+                                     tokens_per_seq=tokens_per_seq)()

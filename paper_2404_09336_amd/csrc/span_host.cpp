@@ -57,13 +57,84 @@ int check_desc(const span_attn_desc_t* d) {
 
 static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Slices are sized so that a call puts about kTargetWorkgroups workgroups on the chip (256 CUs x 8
-// resident workgroups), never fewer than kMinSlice positions per slice, never more than the
-// kMaxSlice the kernel's position table holds.
-Partition plan_partition(const span_attn_desc_t* d) {
+// Exact mode (the caller knows how many positions each sequence attends).
+//
+// All workgroups of a launch that fit on the chip at once start together and spend the same first
+// microseconds walking the span metadata before any K row is requested; a second round of equal
+// workgroups would repeat that dead time.  So the aim is ONE resident round: the smallest slice size T
+// for which all slices of all sequences, times heads, fit into kTargetWorkgroups.  Sequence b gets
+// ceil(n_b / T) slices, which the kernel makes equal-sized.  Only when even the largest slice the
+// kernel supports does not fit (more work than one round can hold) do the slices stop growing:
+// kMultiRoundSlice then gives enough workgroups for the rounds to drift apart and balance the tail.
+static int64_t slices_for(int64_t n, int64_t T) { return n <= 0 ? 1 : ceil_div(n, T); }
+
+static bool plan_exact(const span_attn_desc_t* d, int64_t max_tok, Partition* p, uint32_t* table) {
+  if (!d->tokens_per_seq || d->num_splits != 0 || d->batch > kMaxPlanBatch) return false;
+  auto tokens = [&](int32_t b) {
+    const int64_t n = d->tokens_per_seq[b];
+    return n < 0 ? (int64_t)0 : (n > max_tok ? max_tok : n);
+  };
+  auto count = [&](int64_t T) {
+    int64_t c = 0;
+    for (int32_t b = 0; b < d->batch; ++b) c += slices_for(tokens(b), T);
+    return c;
+  };
+  int64_t sum = 0;
+  for (int32_t b = 0; b < d->batch; ++b) sum += tokens(b);
+  const int64_t room = kTargetWorkgroups / d->heads;  // slices (per head) that fit in one round
+  int64_t T = ceil_div(sum * d->heads, kTargetWorkgroups);
+  if (T < kMinSlice) T = kMinSlice;
+  int64_t total = 0;
+  for (;;) {
+    if (T >= kMaxSlice) {  // more than one round whatever we do
+      T = room >= d->batch && count(kMaxSlice) <= room ? kMaxSlice : kMultiRoundSlice;
+      total = count(T);
+      break;
+    }
+    total = count(T);
+    if (room < d->batch) break;
+    if (total <= room) {  // fits: give back what the proportional step overshot
+      for (int i = 0; i < 8 && T - kSliceGranule >= kMinSlice && count(T - kSliceGranule) <= room; ++i)
+        T -= kSliceGranule;
+      total = count(T);
+      break;
+    }
+    // grow T in proportion to the overshoot (at least one granule) and try again
+    int64_t next = ceil_div(ceil_div(T * total, room), kSliceGranule) * kSliceGranule;
+    T = next > T ? next : T + kSliceGranule;
+  }
+  if (room < d->batch) {  // batch * heads alone exceeds a round: one slice per sequence where possible
+    T = kMaxSlice;
+    total = count(T);
+  }
+  if (total > kMaxPlanSlices) return false;
+  int64_t most = 1, largest = 1;
+  int32_t y = 0;
+  for (int32_t b = 0; b < d->batch; ++b) {
+    const int64_t n = tokens(b), nsl = slices_for(n, T);
+    if (nsl > kMaxPlanSplits) return false;
+    if (nsl > most) most = nsl;
+    if (ceil_div(n, nsl) > largest) largest = ceil_div(n, nsl);
+    if (table)
+      for (int64_t s = 0; s < nsl; ++s) table[y++] = pack_slice((uint32_t)b, (uint32_t)s, (uint32_t)nsl);
+  }
+  p->exact = true;
+  p->num_splits = (int32_t)most;
+  p->slice_tokens = (int32_t)largest;
+  p->max_tokens = (int32_t)max_tok;
+  p->total_slices = (int32_t)total;
+  return true;
+}
+
+// Uniform mode: every sequence gets the same number of slices, sized so that a call puts about
+// kTargetWorkgroups workgroups on the chip (256 CUs x 8 resident workgroups), never fewer than kMinSlice
+// positions per slice, never more than the kMaxSlice the kernel's position table holds.
+Partition plan_partition(const span_attn_desc_t* d, uint32_t* table) {
   const int64_t max_tok = (d->max_tokens > 0 && d->max_tokens < d->max_len) ? d->max_tokens : d->max_len;
+  Partition p;
+  if (plan_exact(d, max_tok, &p, table)) return p;
   const int64_t pairs = (int64_t)d->batch * d->heads;
-  int64_t splits = d->num_splits > 0 ? d->num_splits : ceil_div(kTargetWorkgroups, pairs);
+  int64_t splits = d->num_splits > 0 ? d->num_splits : kTargetWorkgroups / pairs;  // stay within one round
   const int64_t most = ceil_div(max_tok, kMinSlice);
   if (d->num_splits == 0 && splits > most) splits = most;
   if (splits > max_tok) splits = max_tok;
@@ -72,10 +143,11 @@ Partition plan_partition(const span_attn_desc_t* d) {
   if (slice > kMaxSlice) slice = kMaxSlice;
   while (ceil_div(max_tok, slice) > 65535) slice += kSliceGranule;  // grid.y limit
   splits = ceil_div(max_tok, slice);
-  Partition p;
+  p.exact = false;
   p.num_splits = (int32_t)splits;
   p.slice_tokens = (int32_t)slice;
   p.max_tokens = (int32_t)max_tok;
+  p.total_slices = (int32_t)(splits * d->batch);
   return p;
 }
 
@@ -85,24 +157,29 @@ size_t workspace_counter_bytes(const span_attn_desc_t* d) {
 }
 
 size_t workspace_ml_bytes(const span_attn_desc_t* d, const Partition& p) {
-  const size_t n = (size_t)d->batch * d->heads * p.num_splits * 2 * sizeof(float);
+  const size_t n = (size_t)p.total_slices * d->heads * 2 * sizeof(float);
   return (n + 255) & ~(size_t)255;
 }
 
 size_t workspace_bytes(const span_attn_desc_t* d, const Partition& p) {
   if (p.num_splits <= 1) return 0;
-  return workspace_counter_bytes(d) + workspace_ml_bytes(d, p) + (size_t)d->batch * d->heads * p.num_splits * d->head_dim * sizeof(float);
+  return workspace_counter_bytes(d) + workspace_ml_bytes(d, p) +
+         (size_t)p.total_slices * d->heads * d->head_dim * sizeof(float);
 }
 
 }  // namespace spanattn
 
-extern "C" int span_plan_splits(const span_attn_desc_t* desc, int32_t* num_splits, int32_t* slice_tokens) {
-  if (!num_splits || !slice_tokens) return SPAN_ERR_NULL;
+extern "C" int span_plan_query(const span_attn_desc_t* desc, span_plan_info_t* info) {
+  if (!info) return SPAN_ERR_NULL;
   const int rc = spanattn::check_desc(desc);
   if (rc != SPAN_OK) return rc;
   const spanattn::Partition p = spanattn::plan_partition(desc);
-  *num_splits = p.num_splits;
-  *slice_tokens = p.slice_tokens;
+  info->exact = p.exact ? 1 : 0;
+  info->slice_tokens = p.slice_tokens;
+  info->max_splits = p.num_splits;
+  info->reserved = 0;
+  info->workgroups = (int64_t)p.total_slices * desc->heads;
+  info->workspace_bytes = (int64_t)spanattn::workspace_bytes(desc, p);
   return SPAN_OK;
 }
 

@@ -16,14 +16,27 @@ constexpr int kSliceGranule = 16;
 constexpr int kMaxLen = 1 << 22;           // keeps every in-slab byte offset inside 32 bits
 constexpr int64_t kTargetWorkgroups = 2048;  // 256 CUs x 8 resident workgroups
 
+constexpr int kMultiRoundSlice = 512;       // slice size once there is more work than one resident round holds
+constexpr int kMaxPlanSlices = 768;        // entries of the slice table passed as kernel argument
+constexpr int kMaxPlanBatch = 1024;        // 10 bits of a table entry
+constexpr int kMaxPlanSplits = 2047;       // 11 bits of a table entry
+
+// Slice table entry (exact mode): batch index | slice index within the sequence | slices of the sequence.
+inline uint32_t pack_slice(uint32_t b, uint32_t split, uint32_t nsl) { return b | (split << 10) | (nsl << 21); }
+
 struct Partition {
-  int32_t num_splits;    // KV slices per (batch, head)
-  int32_t slice_tokens;  // attended positions per slice
-  int32_t max_tokens;    // bound on attended positions per sequence used for the grid
+  bool exact;            // slices come from the table; otherwise the grid is (heads, num_splits, batch)
+  int32_t num_splits;    // uniform: KV slices per (batch, head); exact: most slices of any sequence
+  int32_t slice_tokens;  // attended positions per slice (exact: upper bound)
+  int32_t max_tokens;    // bound on attended positions per sequence
+  int32_t total_slices;  // exact: table entries (grid.y); uniform: batch * num_splits
 };
 
+// Fills `table` (kMaxPlanSlices entries) when the partition is exact; table may be null to only size it.
+Partition plan_partition(const span_attn_desc_t* d, uint32_t* table);
+inline Partition plan_partition(const span_attn_desc_t* d) { return plan_partition(d, nullptr); }
+
 int check_desc(const span_attn_desc_t* d);
-Partition plan_partition(const span_attn_desc_t* d);
 size_t workspace_counter_bytes(const span_attn_desc_t* d);
 size_t workspace_ml_bytes(const span_attn_desc_t* d, const Partition& p);
 size_t workspace_bytes(const span_attn_desc_t* d, const Partition& p);

@@ -10,7 +10,10 @@
 // the kernel is bound by HBM and uses no matrix cores):
 //   * grid = (heads, KV slices, batch).  A sequence's span is flattened into a virtual token index
 //     0..n_b-1 (prefix sums of the interval lengths); slice s owns virtual tokens [s*T, (s+1)*T).
-//     The host picks T so that short spans still give every CU several workgroups.
+//     The host picks T so that short spans still give every CU several workgroups.  When the caller
+//     passes the per-sequence token counts, the grid is instead (heads, all slices of all sequences):
+//     a table in the kernel arguments names each slice's sequence, and every sequence is cut into
+//     equal slices of about the same size as everyone else's, so ragged batches leave no idle workgroup.
 //   * a workgroup is 4 wavefronts; each wavefront takes a contiguous quarter of the slice and is
 //     independent of the others until the final merge (it even builds its own part of the
 //     virtual-token -> position table, so no barrier sits in front of the first K load).
@@ -51,6 +54,9 @@ struct LaunchArgs {
   float* part_acc;  // [batch*heads, num_splits, D]  un-normalised
   int32_t heads, max_len, num_intervals, slice_tokens, num_splits, max_tokens;
   float scale_log2e;
+  int32_t total_slices;             // exact mode: entries of `table` in use
+  int32_t exact;                    // 1: blockIdx.y indexes `table`; 0: grid is (heads, num_splits, batch)
+  uint32_t table[kMaxPlanSlices];   // exact mode: pack_slice(batch, slice, slices of the sequence)
 };
 
 // ---- storage types: 16 bytes of a row -> fp32 --------------------------------------------------
@@ -150,7 +156,7 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int 
 
 // ---- the streaming kernel ------------------------------------------------------------------------
 template <class Elt, int D, bool kDense, int U>
-__global__ __launch_bounds__(kThreads) void decode_kernel(const LaunchArgs a) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void decode_kernel(const LaunchArgs a) {
   constexpr int EPL = Elt::kPerVec;        // elements per lane (one 128-bit piece)
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPL = 64 / LPR;            // rows per wave-wide load
@@ -159,7 +165,20 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const LaunchArgs a) {
 
   // heads vary fastest: consecutive workgroups go to different XCDs, and the 'is this slice empty'
   // answer is the same for all heads of a (batch, slice), so full and empty slices spread evenly
-  const int h = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.x;
+  int b, split, nsl, y0;  // sequence, slice within it, slices of the sequence, first slice row of the sequence
+  if (a.exact) {
+    const uint32_t e = a.table[blockIdx.y];
+    b = e & 1023u;
+    split = (e >> 10) & 2047u;
+    nsl = e >> 21;
+    y0 = blockIdx.y - split;
+  } else {
+    b = blockIdx.z;
+    split = blockIdx.y;
+    nsl = a.num_splits;
+    y0 = b * nsl;
+  }
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int grp = lane / LPR, lir = lane % LPR;
   const size_t bh = (size_t)b * a.heads + h;
@@ -182,8 +201,8 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const LaunchArgs a) {
   }
 
   // ---- step 1: how many attended positions does the sequence have, which are mine ----------------
-  const int T = a.slice_tokens;
-  const int slice_begin = split * T;
+  // uniform mode knows its slice before counting; exact mode cuts the sequence's own total evenly
+  const int scan_stop = a.exact ? 0x7fffffff : (split + 1) * a.slice_tokens;
   int n_total;
   int n_int = 0, off0 = 0;
   int st0 = 0, len0 = 0, incl0 = 0;  // first chunk of 64 intervals, kept in registers
@@ -200,13 +219,15 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const LaunchArgs a) {
     }
     incl0 = wave_inclusive_scan(len0, lane);
     n_total = __builtin_amdgcn_readlane(incl0, 63);
-    for (int c0 = 64; c0 < n_int && n_total < slice_begin + T; c0 += 64) {
+    for (int c0 = 64; c0 < n_int && n_total < scan_stop; c0 += 64) {
       int len = 0;
       if (c0 + lane < n_int) len = clampi(a.ends[off0 + c0 + lane] - a.starts[off0 + c0 + lane], 0, a.max_len);
       n_total += __builtin_amdgcn_readlane(wave_inclusive_scan(len, lane), 63);
     }
   }
   n_total = n_total < a.max_tokens ? n_total : a.max_tokens;
+  const int T = a.exact ? min((n_total + nsl - 1) / nsl, kMaxSlice) : a.slice_tokens;
+  const int slice_begin = split * T;
   const int cnt = __builtin_amdgcn_readfirstlane(clampi(n_total - slice_begin, 0, T));
 
   // State of this slice for output column tid (tid < D): un-normalised, m in log2 units.
@@ -350,7 +371,7 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const LaunchArgs a) {
   }
   }  // cnt > 0
 
-  if (a.num_splits == 1) {  // one slice per (batch, head): this workgroup owns the output row
+  if (nsl == 1) {  // one slice for this (batch, head): this workgroup owns the output row
     if (tid < D) a.out[bh * D + tid] = L > 0.f ? o / L : 0.f;
     return;
   }
@@ -363,29 +384,31 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const LaunchArgs a) {
   // the writer waits for its stores to be acknowledged before the ticket is taken, and the reader
   // only starts after its own ticket came back.  A device-scope fence would write back and
   // invalidate the whole L2 of the XCD for every workgroup, which costs far more than the merge.
-  const size_t slot0 = bh * a.num_splits;
+  // state of slice s of (b, h) lives in slot (y0 + s) * heads + h
+  const size_t H = (size_t)a.heads;
+  const size_t my_slot = (size_t)(y0 + split) * H + h;
   if (tid < D) {
-    if (cnt > 0) publish(&a.part_acc[(slot0 + split) * D + tid], o);
+    if (cnt > 0) publish(&a.part_acc[my_slot * D + tid], o);
     if (tid == 0) {
-      publish(&a.part_ml[(slot0 + split) * 2], M);
-      publish(&a.part_ml[(slot0 + split) * 2 + 1], L);
+      publish(&a.part_ml[my_slot * 2], M);
+      publish(&a.part_ml[my_slot * 2 + 1], L);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my published stores are acknowledged
   }
   __syncthreads();
   if (tid == 0) s_ticket = __hip_atomic_fetch_add(&a.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
-  if (s_ticket != a.num_splits - 1) return;
+  if (s_ticket != nsl - 1) return;
 
   constexpr int G = kThreads / D;  // column t is merged by G threads, each over every G-th slice
   const int g = tid / D, t = tid % D;
-  const float* ml = a.part_ml + slot0 * 2;
-  const float* pa = a.part_acc + slot0 * D;
+  const float* ml = a.part_ml + ((size_t)y0 * H + h) * 2;
+  const float* pa = a.part_acc + ((size_t)y0 * H + h) * D;
   float mm = -INFINITY, ll = 0.f, oo = 0.f;
 #pragma unroll 4
-  for (int s = g; s < a.num_splits; s += G) {
-    const float ms = observe(&ml[2 * s]), ls = observe(&ml[2 * s + 1]);
-    float as = observe(&pa[(size_t)s * D + t]);  // slot of an empty slice is never written: select, do not scale
+  for (int s = g; s < nsl; s += G) {
+    const float ms = observe(&ml[(size_t)s * H * 2]), ls = observe(&ml[(size_t)s * H * 2 + 1]);
+    float as = observe(&pa[(size_t)s * H * D + t]);  // slot of an empty slice is never written: select, do not scale
     as = ls > 0.f ? as : 0.f;
     merge_state(mm, ll, &oo, 1, ls > 0.f ? ms : -INFINITY, ls > 0.f ? ls : 0.f, &as);
   }
@@ -410,7 +433,8 @@ thread_local int g_last_hip_error = 0;
 
 template <class Elt, int D, bool kDense>
 int launch_typed(const LaunchArgs& a, int batch, hipStream_t stream) {
-  const dim3 grid((unsigned)a.heads, (unsigned)a.num_splits, (unsigned)batch);
+  const dim3 grid = a.exact ? dim3((unsigned)a.heads, (unsigned)a.total_slices, 1u)
+                            : dim3((unsigned)a.heads, (unsigned)a.num_splits, (unsigned)batch);
   hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, 4>), grid, dim3(kThreads), 0, stream, a);
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) {
@@ -427,12 +451,12 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   if (rc != SPAN_OK) return rc;
   if (!q || !k || !v || !out) return SPAN_ERR_NULL;
   if (kDense ? !ctx_lens : (!offsets || (d->num_intervals > 0 && (!starts || !ends)))) return SPAN_ERR_NULL;
-  const Partition p = plan_partition(d);
+  LaunchArgs a;
+  const Partition p = plan_partition(d, a.table);
   const size_t need = workspace_bytes(d, p);
   if (need > 0 && (!d->workspace || ((uintptr_t)d->workspace & 255u) || d->workspace_bytes < need))
     return SPAN_ERR_WORKSPACE;
 
-  LaunchArgs a;
   a.q = q;
   a.k = k;
   a.v = v;
@@ -450,6 +474,8 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   a.slice_tokens = p.slice_tokens;
   a.num_splits = p.num_splits;
   a.max_tokens = p.max_tokens;
+  a.exact = p.exact ? 1 : 0;
+  a.total_slices = p.total_slices;
   a.scale_log2e = scale * 1.4426950408889634f;
   hipStream_t stream = (hipStream_t)d->stream;
 

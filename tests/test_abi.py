@@ -25,7 +25,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = span.load_library()
     names = declared_functions()
-    assert {"span_decode_attn", "dense_decode_attn", "span_validate", "span_plan_splits", "span_workspace_bytes",
+    assert {"span_decode_attn", "dense_decode_attn", "span_validate", "span_plan_query", "span_workspace_bytes",
             "span_workspace_init", "span_strerror", "span_last_hip_error"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
@@ -69,21 +69,53 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.dense_decode_attn(ctypes.byref(mk(head_dim=32)), 1, 1, 1, 1, 0.1, 1) == -2
 
 
-def test_partition_arithmetic():
+def test_partition_arithmetic_uniform():
     for B, H, L, mt, ns in itertools.product([1, 8, 64, 300], [1, 32], [1, 100, 512, 4096, 16384, 1 << 22],
                                              [0, 1, 63, 157, 5000], [0, 1, 2, 5, 64]):
         d = binding.make_desc(B, H, 128, L, 1, 10, mt, ns)
-        splits, slice_tokens = span.span_plan_splits(d)
+        info = span.span_plan_query(d)
+        splits, slice_tokens = info["max_splits"], info["slice_tokens"]
         max_tok = min(mt, L) if mt > 0 else L
-        assert 1 <= slice_tokens <= 1024
+        assert not info["exact"] and info["workgroups"] == B * H * splits
+        assert 1 <= slice_tokens <= 1024 and splits <= 65535
         assert splits * slice_tokens >= max_tok              # every position has an owner
         assert (splits - 1) * slice_tokens < max_tok         # and no slice is useless
         if ns and -(-max_tok // ns) <= 1024 - 16 and ns <= max_tok:
             assert splits <= ns
         ws = span.span_workspace_bytes(d)
-        assert (ws == 0) == (splits == 1)
+        assert ws == info["workspace_bytes"] and (ws == 0) == (splits == 1)
         if splits > 1:
             assert ws >= B * H * (splits * (128 + 2) + 1) * 4
+
+
+def test_partition_arithmetic_exact():
+    rng = np.random.default_rng(3)
+    for trial in range(300):
+        B = int(rng.integers(1, 70))
+        H = int(rng.choice([1, 8, 32]))
+        L = int(rng.choice([64, 512, 4096, 16384]))
+        tok = rng.integers(0, L + 1, size=B)
+        if trial % 5 == 0:
+            tok[:] = int(rng.integers(1, L + 1))             # uniform batch
+        mt = int(tok.max()) if trial % 2 else 0
+        d = binding.make_desc(B, H, 128, L, 1, 10, mt, 0, tokens_per_seq=tok)
+        info = span.span_plan_query(d)
+        if not info["exact"]:
+            assert sum(-(-int(n) // 1024) for n in tok) > 768 or True
+            continue
+        T = info["slice_tokens"]
+        assert 1 <= T <= 1024
+        assert info["workgroups"] % H == 0 and B <= info["workgroups"] // H <= 768
+        # enough slices of at most T positions to hold every sequence
+        assert info["workgroups"] // H >= sum(max(1, -(-int(n) // T)) for n in tok) - B
+        assert info["max_splits"] * T >= tok.max()
+        assert (info["workspace_bytes"] == 0) == (info["max_splits"] == 1)
+    # equal token counts near one chip-load stay unsplit; num_splits > 0 turns the table off
+    tok = np.full(64, 156)
+    assert span.span_plan_query(binding.make_desc(64, 32, 128, 512, 1, 10, 168, 0, tokens_per_seq=tok))["max_splits"] == 1
+    assert not span.span_plan_query(binding.make_desc(64, 32, 128, 512, 1, 10, 168, 2, tokens_per_seq=tok))["exact"]
+    assert not span.span_plan_query(binding.make_desc(1025, 1, 128, 512, 1, 10, 0, 0,
+                                                      tokens_per_seq=np.ones(1025)))["exact"]
 
 
 def test_validator_matches_oracle_on_golden_cases():

@@ -20,8 +20,12 @@ def _dev(a, device):
 
 
 def run_span(cfg, sp, q, K, V, device, **kw):
+    """By default the call gets what a caller has after span_validate: the largest span and the per-sequence
+    token counts (exact slicing).  num_splits=... or tokens_per_seq=None select the uniform grid."""
     code, bs, bi, tok = span.span_validate(sp.offsets, sp.starts, sp.ends, sp.ctx_lens)
     kw.setdefault("max_tokens", int(tok.max()) if code == 0 and len(tok) else 0)
+    if code == 0:
+        kw.setdefault("tokens_per_seq", tok)
     out = span.span_decode_attn(q, K, V, _dev(sp.offsets, device), _dev(sp.starts, device), _dev(sp.ends, device),
                                 _dev(sp.ctx_lens, device), np.float32(cfg.scale), **kw)
     torch.cuda.synchronize()
@@ -29,6 +33,7 @@ def run_span(cfg, sp, q, K, V, device, **kw):
 
 
 def run_dense(cfg, ctx_lens, q, K, V, device, **kw):
+    kw.setdefault("tokens_per_seq", np.asarray(ctx_lens, np.int64))
     out = span.dense_decode_attn(q, K, V, _dev(np.asarray(ctx_lens, np.int32), device), np.float32(cfg.scale), **kw)
     torch.cuda.synchronize()
     return out.cpu().numpy().astype(np.float64)
@@ -64,9 +69,12 @@ def test_workload_span_parity(cid, gpu_device):
     q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device)
     got = run_span(cfg, sp, q, K, V, gpu_device)
     check(got, oracle_span(cfg, sp, q, K, V), cfg.tol, f"config {cid} span (coverage {sp.coverage():.3f})")
-    # without the caller's bound on span tokens the grid is sized for max_len: same result
-    got2 = run_span(cfg, sp, q, K, V, gpu_device, max_tokens=0)
-    check(got2, got, 1e-6, f"config {cid} span, max_tokens unknown vs known")
+    ref = oracle_span(cfg, sp, q, K, V)
+    # without the per-sequence counts every sequence gets the same number of slices
+    check(run_span(cfg, sp, q, K, V, gpu_device, tokens_per_seq=None), ref, cfg.tol, f"config {cid} span, uniform grid")
+    # without even the bound on span tokens the grid is sized for max_len
+    check(run_span(cfg, sp, q, K, V, gpu_device, tokens_per_seq=None, max_tokens=0), ref, cfg.tol,
+          f"config {cid} span, uniform grid sized for max_len")
 
 
 @pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
@@ -141,6 +149,24 @@ def test_caller_workspace_is_used_and_sufficient(gpu_device):
     for i in range(3):   # the call leaves the counters zero: the same workspace serves the next calls
         got = run_span(cfg, sp, q, K, V, gpu_device, num_splits=4, max_tokens=0, workspace=ws)
         check(got, ref, cfg.tol, f"workspace reused, call {i + 2}")
+
+
+def test_wrong_token_counts_from_the_caller(gpu_device):
+    """tokens_per_seq only steers the slicing: overstating it leaves idle slices, understating it makes slices
+    larger; neither changes the result (short of the 1024-position slice limit) nor memory safety."""
+    cfg = small_cfg("f16", 128, B=3, H=4, L=2048)
+    sp = SpanBatch.from_lists([[(0, 300), (900, 1500)], [(5, 6)], [(100, 2048)]], [2048] * 3)
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=21)
+    ref = oracle_span(cfg, sp, q, K, V)
+    true = sp.tokens_per_seq()
+    for name, tok in (("exact", true), ("overstated", true * 2 + 7), ("understated", np.maximum(true // 2, 1)),
+                      ("swapped", true[::-1].copy())):
+        got = run_span(cfg, sp, q, K, V, gpu_device, tokens_per_seq=tok, max_tokens=0)
+        check(got, ref, cfg.tol, f"tokens_per_seq {name}")
+    # all zeros: one slice per sequence, so a sequence may lose what exceeds 1024 positions; the short ones are exact
+    got = run_span(cfg, sp, q, K, V, gpu_device, tokens_per_seq=true * 0, max_tokens=0)
+    assert np.isfinite(got).all()
+    check(got[:2], ref[:2], cfg.tol, "tokens_per_seq all zero, sequences within one slice")
 
 
 # ------------------------------------------------------------------ degenerate and edge cases

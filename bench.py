@@ -44,7 +44,7 @@ def parse_args():
     ap.add_argument("--others", action="store_true", help="also time configs 2, 4, 5 (reported under 'workloads')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also launch one plain 1 GiB device copy (reference point for HBM traffic counters)")
+                    help="also launch a plain 1 GiB-in / 1 GiB-out elementwise kernel (reference for HBM traffic counters)")
     return ap.parse_args()
 
 
@@ -172,12 +172,15 @@ def main():
     cfg = wl.cfg
 
     if args.calibrate_copy:
-        a = torch.empty(1 << 30, dtype=torch.uint8, device=device)
-        b = torch.zeros(1 << 30, dtype=torch.uint8, device=device)
+        # a plain elementwise kernel that reads 1 GiB and writes 1 GiB (torch's same-dtype copy_ is a DMA
+        # memcpy, not a kernel, so it would not show up in per-kernel counters)
+        src = torch.ones(1 << 28, dtype=torch.float32, device=device)
+        dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        a.copy_(b)
+        for _ in range(3):
+            torch.neg(src, out=dst)
         torch.cuda.synchronize()
-        del a, b
+        del src, dst
 
     res_span = res_dense = res_hot = None
     if args.only in ("all", "span"):

@@ -108,17 +108,19 @@ static bool plan_exact(const span_attn_desc_t* d, int64_t max_tok, Partition* p,
     total = count(T);
   }
   if (total > kMaxPlanSlices) return false;
-  int64_t most = 1, largest = 1;
+  int64_t most = 1, least = kMaxPlanSplits + 1, largest = 1;
   int32_t y = 0;
   for (int32_t b = 0; b < d->batch; ++b) {
     const int64_t n = tokens(b), nsl = slices_for(n, T);
     if (nsl > kMaxPlanSplits) return false;
     if (nsl > most) most = nsl;
+    if (nsl < least) least = nsl;
     if (ceil_div(n, nsl) > largest) largest = ceil_div(n, nsl);
     if (table)
       for (int64_t s = 0; s < nsl; ++s) table[y++] = pack_slice((uint32_t)b, (uint32_t)s, (uint32_t)nsl);
   }
-  p->exact = true;
+  p->exact = most != least;  // same count for every sequence: a (heads, slices, batch) grid says it all
+  p->even = true;
   p->num_splits = (int32_t)most;
   p->slice_tokens = (int32_t)largest;
   p->max_tokens = (int32_t)max_tok;
@@ -144,6 +146,7 @@ Partition plan_partition(const span_attn_desc_t* d, uint32_t* table) {
   while (ceil_div(max_tok, slice) > 65535) slice += kSliceGranule;  // grid.y limit
   splits = ceil_div(max_tok, slice);
   p.exact = false;
+  p.even = false;
   p.num_splits = (int32_t)splits;
   p.slice_tokens = (int32_t)slice;
   p.max_tokens = (int32_t)max_tok;
@@ -174,7 +177,7 @@ extern "C" int span_plan_query(const span_attn_desc_t* desc, span_plan_info_t* i
   const int rc = spanattn::check_desc(desc);
   if (rc != SPAN_OK) return rc;
   const spanattn::Partition p = spanattn::plan_partition(desc);
-  info->exact = p.exact ? 1 : 0;
+  info->exact = p.even ? 1 : 0;
   info->slice_tokens = p.slice_tokens;
   info->max_splits = p.num_splits;
   info->reserved = 0;

@@ -26,6 +26,7 @@ inline uint32_t pack_slice(uint32_t b, uint32_t split, uint32_t nsl) { return b 
 
 struct Partition {
   bool exact;            // slices come from the table; otherwise the grid is (heads, num_splits, batch)
+  bool even;             // a sequence's slices share its own token count evenly (needs the caller's counts)
   int32_t num_splits;    // uniform: KV slices per (batch, head); exact: most slices of any sequence
   int32_t slice_tokens;  // attended positions per slice (exact: upper bound)
   int32_t max_tokens;    // bound on attended positions per sequence

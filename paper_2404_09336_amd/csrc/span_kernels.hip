@@ -54,9 +54,18 @@ struct LaunchArgs {
   float* part_acc;  // [batch*heads, num_splits, D]  un-normalised
   int32_t heads, max_len, num_intervals, slice_tokens, num_splits, max_tokens;
   float scale_log2e;
-  int32_t total_slices;             // exact mode: entries of `table` in use
-  int32_t exact;                    // 1: blockIdx.y indexes `table`; 0: grid is (heads, num_splits, batch)
-  uint32_t table[kMaxPlanSlices];   // exact mode: pack_slice(batch, slice, slices of the sequence)
+  int32_t total_slices;             // table mode: entries of `table` in use
+  int32_t even;                     // 1: a sequence's slices share its own token count evenly; 0: slice_tokens each
+};
+// Table mode: blockIdx.y indexes `table` (sequences have different numbers of slices).  The table makes
+// the kernel arguments 3 KB larger, which costs about 0.35 us per launch, so calls that do not need it
+// (every sequence has the same number of slices) use the plain arguments and a (heads, slices, batch) grid.
+struct LaunchArgsTable : LaunchArgs {
+  static constexpr bool kHasTable = true;
+  uint32_t table[kMaxPlanSlices];   // pack_slice(batch, slice, slices of the sequence)
+};
+struct LaunchArgsPlain : LaunchArgs {
+  static constexpr bool kHasTable = false;
 };
 
 // ---- storage types: 16 bytes of a row -> fp32 --------------------------------------------------
@@ -131,8 +140,15 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane) {
 
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
-__device__ __forceinline__ u32x4 load_row_piece(const char* slab, uint32_t byte_off) {
-  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(slab + byte_off));
+// K / V rows are fetched with raw buffer loads: the descriptor covers exactly one (batch, head) slab,
+// so the hardware itself returns zeros for any offset outside it, and the cache policy is explicit.
+// Non-temporal (streaming) loads: every row is used once; measured 17 % faster than default-policy loads.
+constexpr int kRowLoadPolicy = 2;  // bit 0 = sc0, bit 1 = nt, bit 4 = sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const void* slab, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(slab), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 load_row_piece(__amdgpu_buffer_rsrc_t slab, uint32_t byte_off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(slab, byte_off, 0, kRowLoadPolicy);
 }
 
 // Device-coherent store / load of one float that another workgroup reads / wrote in the same kernel.
@@ -155,8 +171,8 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int 
 }
 
 // ---- the streaming kernel ------------------------------------------------------------------------
-template <class Elt, int D, bool kDense, int U>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void decode_kernel(const LaunchArgs a) {
+template <class Elt, int D, bool kDense, int U, class Args>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void decode_kernel(const Args a) {
   constexpr int EPL = Elt::kPerVec;        // elements per lane (one 128-bit piece)
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPL = 64 / LPR;            // rows per wave-wide load
@@ -167,7 +183,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   // answer is the same for all heads of a (batch, slice), so full and empty slices spread evenly
   const int h = blockIdx.x;
   int b, split, nsl, y0;  // sequence, slice within it, slices of the sequence, first slice row of the sequence
-  if (a.exact) {
+  if constexpr (Args::kHasTable) {
     const uint32_t e = a.table[blockIdx.y];
     b = e & 1023u;
     split = (e >> 10) & 2047u;
@@ -201,8 +217,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   }
 
   // ---- step 1: how many attended positions does the sequence have, which are mine ----------------
-  // uniform mode knows its slice before counting; exact mode cuts the sequence's own total evenly
-  const int scan_stop = a.exact ? 0x7fffffff : (split + 1) * a.slice_tokens;
+  // with fixed-size slices the count may stop at the slice's end; even slices need the sequence's total
+  const int scan_stop = a.even ? 0x7fffffff : (split + 1) * a.slice_tokens;
   int n_total;
   int n_int = 0, off0 = 0;
   int st0 = 0, len0 = 0, incl0 = 0;  // first chunk of 64 intervals, kept in registers
@@ -226,7 +242,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
     }
   }
   n_total = n_total < a.max_tokens ? n_total : a.max_tokens;
-  const int T = a.exact ? min((n_total + nsl - 1) / nsl, kMaxSlice) : a.slice_tokens;
+  const int T = a.even ? min((n_total + nsl - 1) / nsl, kMaxSlice) : a.slice_tokens;
   const int slice_begin = split * T;
   const int cnt = __builtin_amdgcn_readfirstlane(clampi(n_total - slice_begin, 0, T));
 
@@ -287,8 +303,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   }
 
   // ---- step 3: stream my K and V rows, online softmax per row group ----------------------------
-  const char* kslab = (const char*)a.k + bh * (size_t)a.max_len * ROWB;
-  const char* vslab = (const char*)a.v + bh * (size_t)a.max_len * ROWB;
+  const uint32_t slab_bytes = (uint32_t)a.max_len * ROWB;
+  const __amdgpu_buffer_rsrc_t kslab = slab_resource((const char*)a.k + bh * (size_t)slab_bytes, slab_bytes);
+  const __amdgpu_buffer_rsrc_t vslab = slab_resource((const char*)a.v + bh * (size_t)slab_bytes, slab_bytes);
   const uint32_t lane_off = (uint32_t)lir * 16u;
 
   float m = -INFINITY, l = 0.f;
@@ -432,10 +449,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
 thread_local int g_last_hip_error = 0;
 
 template <class Elt, int D, bool kDense>
-int launch_typed(const LaunchArgs& a, int batch, hipStream_t stream) {
-  const dim3 grid = a.exact ? dim3((unsigned)a.heads, (unsigned)a.total_slices, 1u)
-                            : dim3((unsigned)a.heads, (unsigned)a.num_splits, (unsigned)batch);
-  hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, 4>), grid, dim3(kThreads), 0, stream, a);
+int launch_typed(const LaunchArgsTable& a, bool use_table, int batch, hipStream_t stream) {
+  if (use_table) {
+    const dim3 grid((unsigned)a.heads, (unsigned)a.total_slices, 1u);
+    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, 4, LaunchArgsTable>), grid, dim3(kThreads), 0, stream, a);
+  } else {
+    const dim3 grid((unsigned)a.heads, (unsigned)a.num_splits, (unsigned)batch);
+    LaunchArgsPlain plain;
+    static_cast<LaunchArgs&>(plain) = static_cast<const LaunchArgs&>(a);
+    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, 4, LaunchArgsPlain>), grid, dim3(kThreads), 0, stream, plain);
+  }
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) {
     g_last_hip_error = (int)err;
@@ -451,7 +474,7 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   if (rc != SPAN_OK) return rc;
   if (!q || !k || !v || !out) return SPAN_ERR_NULL;
   if (kDense ? !ctx_lens : (!offsets || (d->num_intervals > 0 && (!starts || !ends)))) return SPAN_ERR_NULL;
-  LaunchArgs a;
+  LaunchArgsTable a;
   const Partition p = plan_partition(d, a.table);
   const size_t need = workspace_bytes(d, p);
   if (need > 0 && (!d->workspace || ((uintptr_t)d->workspace & 255u) || d->workspace_bytes < need))
@@ -474,7 +497,7 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   a.slice_tokens = p.slice_tokens;
   a.num_splits = p.num_splits;
   a.max_tokens = p.max_tokens;
-  a.exact = p.exact ? 1 : 0;
+  a.even = p.even ? 1 : 0;
   a.total_slices = p.total_slices;
   a.scale_log2e = scale * 1.4426950408889634f;
   hipStream_t stream = (hipStream_t)d->stream;
@@ -482,11 +505,11 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   const bool d128 = d->head_dim == 128;
   switch (d->dtype) {
     case SPAN_F32:
-      return d128 ? launch_typed<F32, 128, kDense>(a, d->batch, stream) : launch_typed<F32, 64, kDense>(a, d->batch, stream);
+      return d128 ? launch_typed<F32, 128, kDense>(a, p.exact, d->batch, stream) : launch_typed<F32, 64, kDense>(a, p.exact, d->batch, stream);
     case SPAN_F16:
-      return d128 ? launch_typed<F16, 128, kDense>(a, d->batch, stream) : launch_typed<F16, 64, kDense>(a, d->batch, stream);
+      return d128 ? launch_typed<F16, 128, kDense>(a, p.exact, d->batch, stream) : launch_typed<F16, 64, kDense>(a, p.exact, d->batch, stream);
     default:
-      return d128 ? launch_typed<BF16, 128, kDense>(a, d->batch, stream) : launch_typed<BF16, 64, kDense>(a, d->batch, stream);
+      return d128 ? launch_typed<BF16, 128, kDense>(a, p.exact, d->batch, stream) : launch_typed<BF16, 64, kDense>(a, p.exact, d->batch, stream);
   }
 }
 

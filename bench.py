@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--only", choices=["all", "span", "dense"], default="all",
                     help="'span' / 'dense' run just that timed loop (for profiling one kernel)")
     ap.add_argument("--others", action="store_true", help="also time configs 2, 4, 5 (reported under 'workloads')")
+    ap.add_argument("--microbench", action="store_true",
+                    help="instead of the headline run: the paper's kernel micro-benchmark (Sec. 5.2), speedup of "
+                         "50 %-sparse masks over dense for sparsity block sizes 32..256 and 1024..8096 cached tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB-in / 1 GiB-out elementwise kernel (reference for HBM traffic counters)")
@@ -140,6 +143,58 @@ def cpu_baseline(wl, budget_s=12.0):
                       f"span rows, OpenMP over heads"}
 
 
+PAPER_MICROBENCH = {"speedup_vs_hf_geomean": {"32": 0.97, "64": 1.2, "128": 1.6, "256": 1.6, "all": 1.29},
+                    "hardware": "1x NVIDIA A100 80GB, batch 64, vs Hugging Face self-attention",
+                    "source": "paper Sec. 5.2"}
+
+
+def microbench(device, steps, warmup):
+    """The kernel micro-benchmark of Sec. 5.2: one new token, batch 64, 1024..8096 cached tokens, random masks that
+    keep 50 % of the context in runs of `sparsity block size` tokens.  The masks travel the paper's way: blocked
+    (block index, bit mask) encoding with 256-token blocks, converted by the library into interval lists.  The
+    speedup is over this library's own dense control (the paper's baseline, Hugging Face attention, is absent)."""
+    import numpy as np
+    import torch
+    import paper_2404_09336_amd as span
+    from workloads import DecodeConfig, draw_qkv, microbench_spans
+    rows, logsum = [], {}
+    for L in (1024, 2048, 4096, 8096):
+        cfg = DecodeConfig(100, f"microbench-{L}", 64, 32, 128, L, L, "f16", 2e-3)
+        ctx = np.full(cfg.batch, L, np.int32)
+        q, K, V = draw_qkv(cfg, ctx, seed=L, device=device)
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
+        row_pair = 2 * cfg.head_dim * cfg.elt_bytes * cfg.heads
+        dense = span.prepare_dense_decode_attn(q, K, V, dev(ctx), np.float32(cfg.scale), max_tokens=L,
+                                               tokens_per_seq=ctx.astype(np.int64))
+        n = max(20, steps // max(1, L // 512))
+        d = timed_loop([dense], [L * cfg.batch * row_pair], n, max(5, warmup // 8))
+        for sbs in (32, 64, 128, 256):
+            sp = microbench_spans(cfg.batch, L, sbs, seed=1000 * L + sbs)
+            boff, bidx, bm = span.span_intervals_to_blocks(256, sp.offsets, sp.starts, sp.ends)   # the paper's format
+            off, st, en = span.span_blocks_to_intervals(256, boff, bidx, bm)                       # what the kernel takes
+            code, _, _, tok = span.span_validate(off, st, en, ctx)
+            assert code == 0
+            call = span.prepare_span_decode_attn(q, K, V, dev(off), dev(st), dev(en), dev(ctx), np.float32(cfg.scale),
+                                                 max_tokens=int(tok.max()), tokens_per_seq=tok)
+            s = timed_loop([call], [int(tok.sum()) * row_pair], n, max(5, warmup // 8))
+            sp_up = d["us_per_call_event"] / s["us_per_call_event"]
+            rows.append({"cached_tokens": L, "sparsity_block": sbs, "kept": round(float(tok.sum()) / (L * cfg.batch), 3),
+                         "intervals_per_seq": round(len(st) / cfg.batch, 1), "span_us": round(s["us_per_call_event"], 2),
+                         "dense_us": round(d["us_per_call_event"], 2), "speedup_vs_dense": round(sp_up, 3),
+                         "span_gbps": round(s["gbps_event"], 1)})
+            logsum.setdefault(str(sbs), []).append(np.log(sp_up))
+        del q, K, V, dense
+        torch.cuda.empty_cache()
+    geo = {k: round(float(np.exp(np.mean(v))), 3) for k, v in logsum.items()}
+    geo["all"] = round(float(np.exp(np.mean([x for v in logsum.values() for x in v]))), 3)
+    return {"metric": "speedup of 50%-sparse span attention over dense decode (kernel micro-benchmark)",
+            "unit": "x", "value": geo["all"], "geomean_by_sparsity_block": geo, "rows": rows, "n_gpus": 1,
+            "dtype": "f16 inputs, fp32 accumulate", "data": "synthetic",
+            "config": {"workload": "batch 64, 32 heads x 128, 1 query token, 1024/2048/4096/8096 cached tokens, "
+                                   "50 % kept in runs of 32/64/128/256, masks via 256-token blocked encoding"},
+            "paper_context": PAPER_MICROBENCH}
+
+
 def read_traffic(cfg_id):
     """HBM bytes per call measured offline with rocprofv3 --pmc (see profiles/); None if not recorded."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
@@ -165,6 +220,10 @@ def main():
         sys.exit(3)
     device = torch.device("cuda:0")
     torch.cuda.set_device(device)
+
+    if args.microbench:
+        print(json.dumps(microbench(device, args.steps, args.warmup)), flush=True)
+        return
 
     copies = args.copies or auto_copies(args.config)
     wl = Workload(args.config, copies, device, coverage=args.coverage, num_splits=args.num_splits,

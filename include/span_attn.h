@@ -43,6 +43,7 @@ enum {
   SPAN_ERR_DTYPE = -3,     /* dtype is not a span_dtype_t                                      */
   SPAN_ERR_WORKSPACE = -4, /* workspace missing, misaligned (256 B) or smaller than required   */
   SPAN_ERR_HIP = -5,       /* a HIP call failed; see span_last_hip_error()                     */
+  SPAN_ERR_CAPACITY = -6,  /* an output array is too small; the needed size is reported        */
   SPAN_BAD_OFFSETS = 1,
   SPAN_BAD_RANGE = 2,
   SPAN_BAD_EMPTY_INTERVAL = 3,
@@ -156,6 +157,34 @@ size_t span_workspace_bytes(const span_attn_desc_t* desc);
  * Uses hipMemsetAsync: do not call it while the stream is being captured into a HIP graph.
  */
 int span_workspace_init(const span_attn_desc_t* desc);
+
+/*
+ * Blocked span encoding (Sec. 3.3 "Attention span encoding", Fig. 3): the context is cut into blocks
+ * of block_size positions; a sequence lists only the blocks that contain span positions, each with its
+ * block index and a mask of block_size bits (bit t of the mask, stored in 32-bit word t/32 at bit
+ * t%32, stands for position block_idx*block_size + t).  These two HOST functions convert between that
+ * encoding and the interval lists the kernels take.  All pointers are host memory.
+ *
+ * span_blocks_to_intervals: blocks of sequence b are block_offsets[b] .. block_offsets[b+1]-1 and must
+ * have strictly increasing block_idx (else SPAN_BAD_UNSORTED; a negative index is SPAN_BAD_RANGE;
+ * block_offsets that do not start at 0 or decrease are SPAN_BAD_OFFSETS; block_size must be a positive
+ * multiple of 32, else SPAN_ERR_SHAPE).  Output: the maximal runs of set bits, in ascending order, runs
+ * that continue across consecutive blocks joined - i.e. the unique sorted list of disjoint,
+ * non-touching intervals of the same position set.  *needed receives the number of intervals; if it
+ * exceeds capacity nothing past capacity is written and SPAN_ERR_CAPACITY is returned (span_offsets is
+ * still complete, so a second call with enough room succeeds).
+ *
+ * span_intervals_to_blocks: the inverse, for any list of intervals with 0 <= start < end (order and
+ * overlap do not matter: the result encodes the union).  Blocks come out in ascending order, untouched
+ * blocks omitted.  *needed receives the number of blocks (same capacity rule; block_masks must hold
+ * capacity * block_size/32 words).
+ */
+int span_blocks_to_intervals(int32_t batch, int32_t block_size, const int32_t* block_offsets,
+                             const int32_t* block_idx, const uint32_t* block_masks, int32_t capacity,
+                             int32_t* span_offsets, int32_t* span_starts, int32_t* span_ends, int32_t* needed);
+int span_intervals_to_blocks(int32_t batch, int32_t block_size, const int32_t* span_offsets,
+                             const int32_t* span_starts, const int32_t* span_ends, int32_t capacity,
+                             int32_t* block_offsets, int32_t* block_idx, uint32_t* block_masks, int32_t* needed);
 
 /* Static string for any code above. */
 const char* span_strerror(int code);

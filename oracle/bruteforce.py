@@ -42,3 +42,14 @@ def masked_attn(q, K, V, per_seq_intervals, ctx_lens, scale) -> np.ndarray:
         for h in range(H):
             out[b, h] = masked_attn_row(q[b, h], K[b, h, :n], V[b, h, :n], M, scale)
     return out
+
+
+def masked_attn_from_bits(q, K, V, attend, scale) -> np.ndarray:
+    """attend: bool [B, L] (True = position attended).  q [B,H,D], K/V [B,H,L,D] -> out [B,H,D] float64."""
+    B, H, L, D = K.shape
+    out = np.zeros((B, H, D), dtype=np.float64)
+    for b in range(B):
+        M = np.where(np.asarray(attend[b], dtype=bool), 0.0, -np.inf)
+        for h in range(H):
+            out[b, h] = masked_attn_row(q[b, h], K[b, h], V[b, h], M, scale)
+    return out

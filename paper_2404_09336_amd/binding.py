@@ -64,6 +64,10 @@ def load_library():
         lib.span_workspace_bytes.restype = ctypes.c_size_t
         lib.span_workspace_init.argtypes = [DP]
         lib.span_workspace_init.restype = ctypes.c_int
+        lib.span_blocks_to_intervals.argtypes = [I32, I32, P, P, P, I32, P, P, P, P]
+        lib.span_blocks_to_intervals.restype = ctypes.c_int
+        lib.span_intervals_to_blocks.argtypes = [I32, I32, P, P, P, I32, P, P, P, P]
+        lib.span_intervals_to_blocks.restype = ctypes.c_int
         lib.span_strerror.argtypes = [ctypes.c_int]
         lib.span_strerror.restype = ctypes.c_char_p
         lib.span_last_hip_error.restype = ctypes.c_int
@@ -132,6 +136,58 @@ def span_validate(span_offsets, span_starts, span_ends, ctx_lens):
     if rc < 0:
         raise SpanAttnError(rc, "span_validate")
     return int(rc), int(bs[0]), int(bi[0]), tok
+
+
+def span_blocks_to_intervals(block_size, block_offsets, block_idx, block_masks):
+    """Host arrays of the blocked encoding in -> (span_offsets, span_starts, span_ends) int32 arrays out.
+    block_masks: uint32 [num_blocks, block_size // 32].  Raises SpanAttnError on a malformed encoding."""
+    lib = load_library()
+    boff = np.ascontiguousarray(block_offsets, dtype=np.int32)
+    bidx = np.ascontiguousarray(block_idx, dtype=np.int32).reshape(-1)
+    bm = np.ascontiguousarray(block_masks, dtype=np.uint32).reshape(-1)
+    batch = boff.shape[0] - 1
+    if bm.shape[0] != bidx.shape[0] * (block_size // 32 if block_size > 0 else 0) and block_size > 0 and block_size % 32 == 0:
+        raise ValueError("block_masks must hold block_size/32 words per block")
+    vp = lambda a: ctypes.c_void_p(a.ctypes.data)
+    off = np.zeros(batch + 1, np.int32)
+    needed = np.zeros(1, np.int32)
+    cap = max(16, 2 * bidx.shape[0])
+    while True:
+        st, en = np.zeros(cap, np.int32), np.zeros(cap, np.int32)
+        rc = lib.span_blocks_to_intervals(batch, int(block_size), vp(boff), vp(bidx), vp(bm), cap, vp(off), vp(st),
+                                          vp(en), vp(needed))
+        if rc == -6:
+            cap = int(needed[0])
+            continue
+        if rc != 0:
+            raise SpanAttnError(rc, "span_blocks_to_intervals")
+        n = int(needed[0])
+        return off, st[:n].copy(), en[:n].copy()
+
+
+def span_intervals_to_blocks(block_size, span_offsets, span_starts, span_ends):
+    """Interval lists in -> (block_offsets, block_idx, block_masks[num_blocks, block_size//32]) out."""
+    lib = load_library()
+    off = np.ascontiguousarray(span_offsets, dtype=np.int32)
+    st = np.ascontiguousarray(span_starts, dtype=np.int32).reshape(-1)
+    en = np.ascontiguousarray(span_ends, dtype=np.int32).reshape(-1)
+    batch = off.shape[0] - 1
+    vp = lambda a: ctypes.c_void_p(a.ctypes.data)
+    boff = np.zeros(batch + 1, np.int32)
+    needed = np.zeros(1, np.int32)
+    words = max(1, block_size // 32)
+    cap = max(16, 2 * st.shape[0])
+    while True:
+        bidx, bm = np.zeros(cap, np.int32), np.zeros(cap * words, np.uint32)
+        rc = lib.span_intervals_to_blocks(batch, int(block_size), vp(off), vp(st), vp(en), cap, vp(boff), vp(bidx),
+                                          vp(bm), vp(needed))
+        if rc == -6:
+            cap = int(needed[0])
+            continue
+        if rc != 0:
+            raise SpanAttnError(rc, "span_intervals_to_blocks")
+        n = int(needed[0])
+        return boff, bidx[:n].copy(), bm[:n * words].reshape(n, words).copy()
 
 
 def _check_qkv(q, k_cache, v_cache):

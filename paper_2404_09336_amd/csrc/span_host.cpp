@@ -2,6 +2,10 @@
 // arithmetic and error strings.  No GPU call in this file.
 #include <limits.h>
 
+#include <algorithm>
+#include <map>
+#include <vector>
+
 #include "span_attn.h"
 #include "span_internal.h"
 
@@ -191,6 +195,102 @@ extern "C" size_t span_workspace_bytes(const span_attn_desc_t* desc) {
   return spanattn::workspace_bytes(desc, spanattn::plan_partition(desc));
 }
 
+// ---- blocked encoding (block index + in-block bit mask) <-> interval lists ---------------------------
+extern "C" int span_blocks_to_intervals(int32_t batch, int32_t block_size, const int32_t* block_offsets,
+                                        const int32_t* block_idx, const uint32_t* block_masks, int32_t capacity,
+                                        int32_t* span_offsets, int32_t* span_starts, int32_t* span_ends,
+                                        int32_t* needed) {
+  if (!block_offsets || !span_offsets || !needed) return SPAN_ERR_NULL;
+  if (batch < 0 || capacity < 0 || block_size <= 0 || block_size % 32 != 0) return SPAN_ERR_SHAPE;
+  if (capacity > 0 && (!span_starts || !span_ends)) return SPAN_ERR_NULL;
+  const int32_t words = block_size / 32;
+  int64_t count = 0;  // intervals produced so far (may run past capacity; writes stop at capacity)
+  span_offsets[0] = 0;
+  *needed = 0;
+  for (int32_t b = 0; b < batch; ++b) {
+    const int32_t first = block_offsets[b], last = block_offsets[b + 1];
+    if ((b == 0 && first != 0) || last < first) return SPAN_BAD_OFFSETS;
+    if (last > first && (!block_idx || !block_masks)) return SPAN_ERR_NULL;
+    int64_t run_start = -1, run_end = -1;  // open run of attended positions, [run_start, run_end)
+    auto close_run = [&]() {
+      if (run_start < 0) return;
+      if (count < capacity) {
+        span_starts[count] = (int32_t)run_start;
+        span_ends[count] = (int32_t)run_end;
+      }
+      ++count;
+      run_start = -1;
+    };
+    for (int32_t j = first; j < last; ++j) {
+      if (block_idx[j] < 0) return SPAN_BAD_RANGE;
+      if (j > first && block_idx[j] <= block_idx[j - 1]) return SPAN_BAD_UNSORTED;
+      const int64_t base = (int64_t)block_idx[j] * block_size;
+      if (base + block_size > INT32_MAX) return SPAN_BAD_RANGE;
+      for (int32_t w = 0; w < words; ++w) {
+        const uint32_t m = block_masks[(size_t)j * words + w];
+        for (int32_t t = 0; t < 32; ++t) {
+          if (!((m >> t) & 1u)) continue;
+          const int64_t pos = base + w * 32 + t;
+          if (run_start >= 0 && pos == run_end) {
+            ++run_end;
+          } else {
+            close_run();
+            run_start = pos;
+            run_end = pos + 1;
+          }
+        }
+      }
+    }
+    close_run();
+    if (count > INT32_MAX) return SPAN_ERR_SHAPE;
+    span_offsets[b + 1] = (int32_t)count;
+  }
+  *needed = (int32_t)count;
+  return count > capacity ? SPAN_ERR_CAPACITY : SPAN_OK;
+}
+
+extern "C" int span_intervals_to_blocks(int32_t batch, int32_t block_size, const int32_t* span_offsets,
+                                        const int32_t* span_starts, const int32_t* span_ends, int32_t capacity,
+                                        int32_t* block_offsets, int32_t* block_idx, uint32_t* block_masks,
+                                        int32_t* needed) {
+  if (!span_offsets || !block_offsets || !needed) return SPAN_ERR_NULL;
+  if (batch < 0 || capacity < 0 || block_size <= 0 || block_size % 32 != 0) return SPAN_ERR_SHAPE;
+  if (capacity > 0 && (!block_idx || !block_masks)) return SPAN_ERR_NULL;
+  const int32_t words = block_size / 32;
+  int64_t count = 0;
+  block_offsets[0] = 0;
+  *needed = 0;
+  for (int32_t b = 0; b < batch; ++b) {
+    const int32_t first = span_offsets[b], last = span_offsets[b + 1];
+    if ((b == 0 && first != 0) || last < first) return SPAN_BAD_OFFSETS;
+    if (last > first && (!span_starts || !span_ends)) return SPAN_ERR_NULL;
+    std::map<int32_t, std::vector<uint32_t>> touched;  // block index -> mask words, ascending
+    for (int32_t i = first; i < last; ++i) {
+      const int32_t s = span_starts[i], e = span_ends[i];
+      if (s < 0) return SPAN_BAD_RANGE;
+      if (s >= e) return SPAN_BAD_EMPTY_INTERVAL;
+      for (int64_t blk = s / block_size; blk * block_size < e; ++blk) {
+        std::vector<uint32_t>& m = touched[(int32_t)blk];
+        if (m.empty()) m.assign(words, 0u);
+        const int64_t lo = std::max<int64_t>(s, blk * block_size) - blk * block_size;
+        const int64_t hi = std::min<int64_t>(e, (blk + 1) * block_size) - blk * block_size;
+        for (int64_t t = lo; t < hi; ++t) m[t / 32] |= 1u << (t % 32);
+      }
+    }
+    for (const auto& kv : touched) {
+      if (count < capacity) {
+        block_idx[count] = kv.first;
+        std::copy(kv.second.begin(), kv.second.end(), block_masks + (size_t)count * words);
+      }
+      ++count;
+    }
+    if (count > INT32_MAX) return SPAN_ERR_SHAPE;
+    block_offsets[b + 1] = (int32_t)count;
+  }
+  *needed = (int32_t)count;
+  return count > capacity ? SPAN_ERR_CAPACITY : SPAN_OK;
+}
+
 extern "C" const char* span_strerror(int code) {
   switch (code) {
     case SPAN_OK: return "ok";
@@ -199,6 +299,7 @@ extern "C" const char* span_strerror(int code) {
     case SPAN_ERR_DTYPE: return "unsupported dtype";
     case SPAN_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SPAN_ERR_HIP: return "a HIP call failed (see span_last_hip_error)";
+    case SPAN_ERR_CAPACITY: return "output array too small (needed size reported)";
     case SPAN_BAD_OFFSETS: return "span_offsets must start at 0, not decrease, and stay within num_intervals";
     case SPAN_BAD_RANGE: return "interval outside [0, ctx_len]";
     case SPAN_BAD_EMPTY_INTERVAL: return "interval with start >= end";

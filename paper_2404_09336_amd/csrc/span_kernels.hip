@@ -56,6 +56,7 @@ struct LaunchArgs {
   float scale_log2e;
   int32_t total_slices;             // table mode: entries of `table` in use
   int32_t even;                     // 1: a sequence's slices share its own token count evenly; 0: slice_tokens each
+  int32_t interleave;               // 1: rows dealt to the waves round-robin (large slices); 0: contiguous quarters
 };
 // Table mode: blockIdx.y indexes `table` (sequences have different numbers of slices).  The table makes
 // the kernel arguments 3 KB larger, which costs about 0.35 us per launch, so calls that do not need it
@@ -249,15 +250,33 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   // State of this slice for output column tid (tid < D): un-normalised, m in log2 units.
   float M = -INFINITY, L = 0.f, o = 0.f;
   if (cnt > 0) {  // same decision in all 4 waves
-  // rows of the slice are dealt to the 4 waves in contiguous, RPL-aligned shares
-  const int rpw = (((cnt + kWavesPerBlock - 1) / kWavesPerBlock) + RPL - 1) / RPL * RPL;
-  const int wb = min(wave * rpw, cnt);
-  const int nrows = min(wb + rpw, cnt) - wb;
-  const int vbeg = slice_begin + wb;  // first virtual token of this wave
+  // How the slice's rows are dealt to the 4 waves.  My rows are numbered r = 0..nrows-1; row r is
+  // virtual token vrow(r) of the sequence.
+  //  * small slices: contiguous quarters (RPL-aligned), four short sequential streams;
+  //  * large slices (a.interleave): units of RPL rows (one load instruction, 1 KiB) dealt round-robin,
+  //    wave w owns units w, w+4, ...  The workgroup then reads one window that moves through the slice.
+  //    Quarters of a large slice are a multiple of the memory-channel interleave apart, so the four
+  //    streams (and those of the neighbouring heads, a power-of-two slab stride away) pile onto the same
+  //    channels: measured 6.1 -> 6.8 TB/s on batch 64 x 1024 cached tokens when dealing round-robin,
+  //    while slices of 100-170 rows are 2-4 % faster with quarters.
+  int nrows, q_first = 0;
+  if (a.interleave) {
+    const int units_all = (cnt + RPL - 1) / RPL;
+    const int units = units_all > wave ? (units_all - wave + kWavesPerBlock - 1) / kWavesPerBlock : 0;
+    const bool own_last = units > 0 && (wave + (units - 1) * kWavesPerBlock) == units_all - 1;
+    nrows = units * RPL - (own_last ? units_all * RPL - cnt : 0);
+  } else {
+    const int rpw = (((cnt + kWavesPerBlock - 1) / kWavesPerBlock) + RPL - 1) / RPL * RPL;
+    q_first = min(wave * rpw, cnt);
+    nrows = min(q_first + rpw, cnt) - q_first;
+  }
+  auto vrow = [&](int r) {
+    return slice_begin + (a.interleave ? ((r / RPL) * kWavesPerBlock + wave) * RPL + (r % RPL) : q_first + r);
+  };
 
   // ---- step 2: virtual token -> KV position for my rows (span path only) -----------------------
   if (!kDense && nrows > 0) {
-    const int vend = vbeg + nrows;
+    const int vbeg = vrow(0), vend = vrow(nrows - 1) + 1;
     int carry = 0;
     for (int c0 = 0; c0 < n_int; c0 += 64) {
       int st = st0, len = len0, incl = incl0;
@@ -281,7 +300,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const int n_here = min(64, n_int - c0);
         for (int r = lane; r < nrows; r += 64) {
-          const int v = vbeg + r;
+          const int v = vrow(r);
           if (v >= carry && v < carry + chunk_total) {
             int idx = 0;  // last interval of the chunk whose exclusive prefix is <= v
 #pragma unroll
@@ -321,7 +340,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
       const int r = base + u * RPL + grp;
       ok[u] = r < nrows;
       const int rc = ok[u] ? r : nrows - 1;  // a row past the end re-reads the last one with weight 0
-      const int p = kDense ? (vbeg + rc) : s_pos[wave][rc];
+      const int p = kDense ? vrow(rc) : s_pos[wave][rc];
       const uint32_t off = (uint32_t)p * ROWB + lane_off;
       kr[u] = load_row_piece(kslab, off);
       vr[u] = load_row_piece(vslab, off);
@@ -498,6 +517,7 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   a.num_splits = p.num_splits;
   a.max_tokens = p.max_tokens;
   a.even = p.even ? 1 : 0;
+  a.interleave = p.slice_tokens >= kInterleaveFrom ? 1 : 0;
   a.total_slices = p.total_slices;
   a.scale_log2e = scale * 1.4426950408889634f;
   hipStream_t stream = (hipStream_t)d->stream;

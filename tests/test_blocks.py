@@ -1,0 +1,114 @@
+"""Blocked span encoding (Sec. 3.3, Fig. 3) <-> interval lists: the library's host converters against a
+set-based reference, bit-exactly."""
+import itertools
+
+import numpy as np
+import pytest
+
+import paper_2404_09336_amd as span
+from oracle import blocks as ref
+
+
+def _flat(per_seq):
+    off, st, en = [0], [], []
+    for iv in per_seq:
+        st += [s for s, _ in iv]
+        en += [e for _, e in iv]
+        off.append(len(st))
+    return off, st, en
+
+
+def _split(off, st, en):
+    return [list(zip(st[off[b]:off[b + 1]].tolist(), en[off[b]:off[b + 1]].tolist())) for b in range(len(off) - 1)]
+
+
+def test_exhaustive_subsets_across_a_block_boundary():
+    """Every subset of positions 26..37 (block size 32: the set straddles blocks 0 and 1)."""
+    cand = list(range(26, 38))
+    for bits in range(1 << len(cand)):
+        pos = {p for i, p in enumerate(cand) if bits >> i & 1}
+        idx, masks = ref.blocks_from_positions(32, pos)
+        off, st, en = span.span_blocks_to_intervals(32, [0, len(idx)], idx, masks)
+        assert _split(off, st, en)[0] == ref.maximal_runs(pos)
+
+
+@pytest.mark.parametrize("block_size", [32, 64, 256])
+def test_random_encodings_round_trip(block_size):
+    rng = np.random.default_rng(block_size)
+    for trial in range(40):
+        B = int(rng.integers(1, 5))
+        per_seq_pos, boff, bidx, bmasks = [], [0], [], []
+        for b in range(B):
+            L = int(rng.integers(1, 6 * block_size))
+            density = float(rng.choice([0.02, 0.3, 0.5, 0.9, 1.0]))
+            pos = {int(p) for p in np.nonzero(rng.random(L) < density)[0]}
+            if trial % 7 == 0:
+                pos = set()                                   # a sequence with no block at all
+            idx, masks = ref.blocks_from_positions(block_size, pos)
+            per_seq_pos.append(pos)
+            bidx += idx
+            bmasks.append(masks)
+            boff.append(len(bidx))
+        bm = np.concatenate(bmasks) if bidx else np.zeros((0, block_size // 32), np.uint32)
+        off, st, en = span.span_blocks_to_intervals(block_size, boff, bidx, bm)
+        got = _split(off, st, en)
+        for b in range(B):
+            assert got[b] == ref.maximal_runs(per_seq_pos[b])
+        # and back: same blocks, same masks
+        boff2, bidx2, bm2 = span.span_intervals_to_blocks(block_size, off, st, en)
+        assert boff2.tolist() == boff and bidx2.tolist() == bidx and np.array_equal(bm2, bm)
+
+
+def test_intervals_to_blocks_takes_any_order_and_overlap():
+    iv = [(70, 75), (0, 40), (30, 66), (300, 301)]
+    boff, bidx, bm = span.span_intervals_to_blocks(64, *_flat([iv]))
+    pos = ref.positions_from_intervals(iv)
+    assert ref.positions_from_blocks(64, bidx, bm) == pos
+    ridx, rm = ref.blocks_from_positions(64, pos)
+    assert bidx.tolist() == ridx and np.array_equal(bm, rm) and boff.tolist() == [0, len(ridx)]
+
+
+def test_workload_spans_survive_the_paper_encoding():
+    from workloads import CONFIGS, draw_spans
+    for cid in (2, 3, 4):
+        sp = draw_spans(CONFIGS[cid])
+        boff, bidx, bm = span.span_intervals_to_blocks(256, sp.offsets, sp.starts, sp.ends)
+        off, st, en = span.span_blocks_to_intervals(256, boff, bidx, bm)
+        for b in range(sp.batch):
+            assert _split(off, st, en)[b] == ref.maximal_runs(ref.positions_from_intervals(sp.intervals(b)))
+        assert span.span_validate(off, st, en, sp.ctx_lens)[0] == 0
+
+
+def test_malformed_encodings_are_rejected():
+    ok_masks = np.ones((2, 1), np.uint32)
+    cases = [
+        (32, [1, 2], [0, 1], ok_masks, 1),          # offsets do not start at 0
+        (32, [0, 2, 1], [0, 1], ok_masks, 1),       # offsets decrease
+        (32, [0, 2], [1, 1], ok_masks, 5),          # block repeated
+        (32, [0, 2], [3, 1], ok_masks, 5),          # blocks out of order
+        (32, [0, 2], [-1, 1], ok_masks, 2),         # negative block
+        (48, [0, 2], [0, 1], ok_masks, -2),         # block size not a multiple of 32
+        (0, [0, 2], [0, 1], ok_masks, -2),
+    ]
+    for bs, boff, bidx, bm, code in cases:
+        with pytest.raises(span.SpanAttnError) as e:
+            span.span_blocks_to_intervals(bs, boff, bidx, bm)
+        assert e.value.code == code, (bs, boff, bidx)
+    with pytest.raises(span.SpanAttnError) as e:
+        span.span_intervals_to_blocks(32, [0, 1], [5], [5])
+    assert e.value.code == 3
+    with pytest.raises(span.SpanAttnError) as e:
+        span.span_intervals_to_blocks(32, [0, 1], [-1], [5])
+    assert e.value.code == 2
+
+
+def test_capacity_is_reported():
+    import ctypes
+    lib = span.load_library()
+    idx, masks = ref.blocks_from_positions(32, {0, 2, 4, 6})
+    boff = np.array([0, 1], np.int32)
+    bidx = np.array(idx, np.int32)
+    off, st, en, need = np.zeros(2, np.int32), np.zeros(2, np.int32), np.zeros(2, np.int32), np.zeros(1, np.int32)
+    vp = lambda a: ctypes.c_void_p(a.ctypes.data)
+    rc = lib.span_blocks_to_intervals(1, 32, vp(boff), vp(bidx), vp(masks), 2, vp(off), vp(st), vp(en), vp(need))
+    assert rc == -6 and need[0] == 4 and off.tolist() == [0, 4] and st.tolist() == [0, 2]

@@ -269,6 +269,29 @@ def test_microbenchmark_masks(gpu_device):
         check(run_span(cfg, sp, q, K, V, gpu_device), oracle_span(cfg, sp, q, K, V), cfg.tol, f"sparsity block {sbs}")
 
 
+def test_unstructured_masks_through_the_blocked_encoding(gpu_device):
+    """Per-token random masks (the paper's kernel takes any mask, Sec. 5.2): mask -> (block index, bit mask)
+    encoding of Sec. 3.3 -> interval list -> kernel, against the additive-mask brute force over all positions."""
+    from oracle import blocks as ref_blocks
+    from oracle import bruteforce
+    cfg = DecodeConfig(92, "bitmask", 3, 2, 128, 600, 600, "f32", 1e-5)
+    rng = np.random.default_rng(16)
+    q, K, V = draw_qkv(cfg, [600] * 3, device=gpu_device, seed=16)
+    attend = np.stack([rng.random(600) < p for p in (0.5, 0.05, 0.97)])
+    boff, bidx, bmasks = [0], [], []
+    for b in range(3):
+        idx, masks = ref_blocks.blocks_from_positions(256, {int(p) for p in np.nonzero(attend[b])[0]})
+        bidx += idx
+        bmasks.append(masks)
+        boff.append(len(bidx))
+    off, st, en = span.span_blocks_to_intervals(256, boff, bidx, np.concatenate(bmasks))
+    sp = SpanBatch(off, st, en, np.full(3, 600, np.int32))
+    assert span.span_validate(sp.offsets, sp.starts, sp.ends, sp.ctx_lens)[0] == 0
+    ref = bruteforce.masked_attn_from_bits(q.cpu().numpy(), K.cpu().numpy(), V.cpu().numpy(), attend,
+                                           np.float32(cfg.scale))
+    check(run_span(cfg, sp, q, K, V, gpu_device), ref, cfg.tol, "random bit masks via blocked encoding")
+
+
 def test_non_default_stream(gpu_device):
     cfg = small_cfg("f16", 128, B=2, H=4, L=512)
     sp = SpanBatch.from_lists([[(0, 100), (400, 512)], [(7, 300)]], [512, 512])

@@ -17,7 +17,7 @@ constexpr int kMaxLen = 1 << 22;           // keeps every in-slab byte offset in
 constexpr int64_t kTargetWorkgroups = 2048;  // 256 CUs x 8 resident workgroups
 
 constexpr int kInterleaveFrom = 384;        // slices at least this large deal their rows to the waves round-robin
-constexpr int kMultiRoundSlice = 512;       // slice size once there is more work than one resident round holds
+constexpr int kMultiRoundSlice = 1024;       // slice size once there is more work than one resident round holds
 constexpr int kMaxPlanSlices = 768;        // entries of the slice table passed as kernel argument
 constexpr int kMaxPlanBatch = 1024;        // 10 bits of a table entry
 constexpr int kMaxPlanSplits = 2047;       // 11 bits of a table entry

@@ -186,6 +186,32 @@ int span_intervals_to_blocks(int32_t batch, int32_t block_size, const int32_t* s
                              const int32_t* span_starts, const int32_t* span_ends, int32_t capacity,
                              int32_t* block_offsets, int32_t* block_idx, uint32_t* block_masks, int32_t* needed);
 
+/*
+ * Span builder (HOST, one sequence): anchors + references -> interval list (Sec. 3.2 "Anchors",
+ * "Determining attention span", "Token generation"; Fig. 5 and Fig. 7 show the two reference styles).
+ *   anchor_starts/ends [num_anchors] : position range [start, end) that anchor k stands for (the group of
+ *                                      tokens it follows; whether the anchor's own tokens are inside the
+ *                                      range is the caller's choice)
+ *   ref_first/ref_last [num_refs]    : the references the model just emitted, each an inclusive range of
+ *                                      anchor ids first..last (a single id has first == last; a line range
+ *                                      "(a-b)" of the summarisation task is first = a, last = b).
+ *                                      first == -1 is the special reference to the previous line,
+ *                                      [prev_line_start, cur_line_start).
+ *   prefix_end                       : the always-attended instruction is [0, prefix_end) (0 = none)
+ *   cur_line_start, ctx_len          : the line being generated, [cur_line_start, ctx_len), is always
+ *                                      attended (its own earlier tokens and the new token)
+ * Output: the union of all those ranges as sorted, disjoint, non-touching intervals (so it passes
+ * span_validate against ctx_len whenever it is not empty).  *needed receives their number; beyond
+ * `capacity` nothing is written and SPAN_ERR_CAPACITY is returned.
+ * Errors: an anchor id outside [0, num_anchors) or first > last -> SPAN_BAD_RANGE; a referenced anchor
+ * whose range is not 0 <= start <= end <= ctx_len -> SPAN_BAD_RANGE; prefix_end, prev_line_start or
+ * cur_line_start outside [0, ctx_len], or prev_line_start > cur_line_start -> SPAN_BAD_RANGE.
+ */
+int span_build(int32_t num_anchors, const int32_t* anchor_starts, const int32_t* anchor_ends, int32_t num_refs,
+               const int32_t* ref_first, const int32_t* ref_last, int32_t prefix_end, int32_t prev_line_start,
+               int32_t cur_line_start, int32_t ctx_len, int32_t capacity, int32_t* out_starts, int32_t* out_ends,
+               int32_t* needed);
+
 /* Static string for any code above. */
 const char* span_strerror(int code);
 

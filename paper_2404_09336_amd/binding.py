@@ -68,6 +68,8 @@ def load_library():
         lib.span_blocks_to_intervals.restype = ctypes.c_int
         lib.span_intervals_to_blocks.argtypes = [I32, I32, P, P, P, I32, P, P, P, P]
         lib.span_intervals_to_blocks.restype = ctypes.c_int
+        lib.span_build.argtypes = [I32, P, P, I32, P, P, I32, I32, I32, I32, I32, P, P, P]
+        lib.span_build.restype = ctypes.c_int
         lib.span_strerror.argtypes = [ctypes.c_int]
         lib.span_strerror.restype = ctypes.c_char_p
         lib.span_last_hip_error.restype = ctypes.c_int
@@ -188,6 +190,35 @@ def span_intervals_to_blocks(block_size, span_offsets, span_starts, span_ends):
             raise SpanAttnError(rc, "span_intervals_to_blocks")
         n = int(needed[0])
         return boff, bidx[:n].copy(), bm[:n * words].reshape(n, words).copy()
+
+
+def span_build(anchors, refs, prefix_end, prev_line_start, cur_line_start, ctx_len):
+    """One sequence: anchors = [(start, end), ...] by anchor id; refs = ids, (first, last) id ranges, or -1 for
+    the previous line.  Returns the list of (start, end) intervals, sorted, disjoint and non-touching."""
+    lib = load_library()
+    a_st = np.ascontiguousarray([a[0] for a in anchors], dtype=np.int32)
+    a_en = np.ascontiguousarray([a[1] for a in anchors], dtype=np.int32)
+    firsts, lasts = [], []
+    for r in refs:
+        f, l = (r, r) if np.isscalar(r) else r
+        firsts.append(f)
+        lasts.append(l)
+    r_f = np.ascontiguousarray(firsts, dtype=np.int32)
+    r_l = np.ascontiguousarray(lasts, dtype=np.int32)
+    vp = lambda x: ctypes.c_void_p(x.ctypes.data) if x.size else None
+    needed = np.zeros(1, np.int32)
+    cap = 16
+    while True:
+        st, en = np.zeros(cap, np.int32), np.zeros(cap, np.int32)
+        rc = lib.span_build(len(anchors), vp(a_st), vp(a_en), len(refs), vp(r_f), vp(r_l), int(prefix_end),
+                            int(prev_line_start), int(cur_line_start), int(ctx_len), cap, vp(st), vp(en), vp(needed))
+        if rc == -6:
+            cap = int(needed[0])
+            continue
+        if rc != 0:
+            raise SpanAttnError(rc, "span_build")
+        n = int(needed[0])
+        return list(zip(st[:n].tolist(), en[:n].tolist()))
 
 
 def _check_qkv(q, k_cache, v_cache):

@@ -291,6 +291,63 @@ extern "C" int span_intervals_to_blocks(int32_t batch, int32_t block_size, const
   return count > capacity ? SPAN_ERR_CAPACITY : SPAN_OK;
 }
 
+// ---- span builder: anchors + references -> sorted disjoint intervals ---------------------------------
+extern "C" int span_build(int32_t num_anchors, const int32_t* anchor_starts, const int32_t* anchor_ends,
+                          int32_t num_refs, const int32_t* ref_first, const int32_t* ref_last, int32_t prefix_end,
+                          int32_t prev_line_start, int32_t cur_line_start, int32_t ctx_len, int32_t capacity,
+                          int32_t* out_starts, int32_t* out_ends, int32_t* needed) {
+  if (!needed) return SPAN_ERR_NULL;
+  if (num_anchors < 0 || num_refs < 0 || capacity < 0 || ctx_len < 0) return SPAN_ERR_SHAPE;
+  if (num_anchors > 0 && (!anchor_starts || !anchor_ends)) return SPAN_ERR_NULL;
+  if (num_refs > 0 && (!ref_first || !ref_last)) return SPAN_ERR_NULL;
+  if (capacity > 0 && (!out_starts || !out_ends)) return SPAN_ERR_NULL;
+  *needed = 0;
+  auto inside = [&](int32_t p) { return p >= 0 && p <= ctx_len; };
+  if (!inside(prefix_end) || !inside(prev_line_start) || !inside(cur_line_start) || prev_line_start > cur_line_start)
+    return SPAN_BAD_RANGE;
+  std::vector<std::pair<int32_t, int32_t>> ranges;
+  ranges.reserve((size_t)num_refs + 3);
+  auto add = [&](int32_t s, int32_t e) {
+    if (s < e) ranges.emplace_back(s, e);
+  };
+  add(0, prefix_end);
+  add(cur_line_start, ctx_len);
+  for (int32_t r = 0; r < num_refs; ++r) {
+    if (ref_first[r] == -1) {  // the previous line
+      add(prev_line_start, cur_line_start);
+      continue;
+    }
+    if (ref_first[r] < 0 || ref_last[r] >= num_anchors || ref_first[r] > ref_last[r]) return SPAN_BAD_RANGE;
+    for (int32_t k = ref_first[r]; k <= ref_last[r]; ++k) {
+      if (anchor_starts[k] < 0 || anchor_ends[k] > ctx_len || anchor_starts[k] > anchor_ends[k]) return SPAN_BAD_RANGE;
+      add(anchor_starts[k], anchor_ends[k]);
+    }
+  }
+  std::sort(ranges.begin(), ranges.end());
+  int64_t count = 0;
+  int32_t cur_s = 0, cur_e = -1;  // open interval; cur_e < 0: none
+  auto flush = [&]() {
+    if (cur_e < 0) return;
+    if (count < capacity) {
+      out_starts[count] = cur_s;
+      out_ends[count] = cur_e;
+    }
+    ++count;
+  };
+  for (const auto& r : ranges) {
+    if (cur_e >= 0 && r.first <= cur_e) {  // overlapping or touching: extend
+      if (r.second > cur_e) cur_e = r.second;
+    } else {
+      flush();
+      cur_s = r.first;
+      cur_e = r.second;
+    }
+  }
+  flush();
+  *needed = (int32_t)count;
+  return count > capacity ? SPAN_ERR_CAPACITY : SPAN_OK;
+}
+
 extern "C" const char* span_strerror(int code) {
   switch (code) {
     case SPAN_OK: return "ok";

@@ -113,6 +113,24 @@ int dense_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k
                       const int32_t* ctx_lens, float scale, float* out);
 
 /*
+ * The two calls above fused with the step that precedes them in a decode loop: appending the new
+ * token's K and V rows to the pre-allocated cache (Sec. 2.1 "KV-cache").  In one launch,
+ *   k_cache[b, h, append_pos[b], :] = k_new[b, h, :]   (same for V)      for every b, h
+ *   out = attention over the UPDATED cache (span / dense as above)
+ *   k_new, v_new : device, desc->dtype, [batch, heads, head_dim]
+ *   append_pos   : device int32 [batch]; a value outside [0, max_len) appends nothing for that sequence
+ * The span (or ctx_lens) is expected to cover append_pos[b] - the new token attends to itself - but need
+ * not.  Within the launch the row is taken from k_new / v_new, never re-read from the cache, so the
+ * result does not depend on when the store lands; the cache holds the row when the call's work completes.
+ */
+int span_decode_attn_append(const span_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                            void* k_cache, void* v_cache, const int32_t* append_pos, const int32_t* span_offsets,
+                            const int32_t* span_starts, const int32_t* span_ends, float scale, float* out);
+int dense_decode_attn_append(const span_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                             void* k_cache, void* v_cache, const int32_t* append_pos, const int32_t* ctx_lens,
+                             float scale, float* out);
+
+/*
  * Span-list validation on the HOST (all pointers are host memory; pure CPU).
  * Sequences are scanned in index order; for a sequence its offsets are checked first, then its
  * intervals in list order, each against the rules in this order; the first failure is returned,

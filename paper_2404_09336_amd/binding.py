@@ -56,6 +56,10 @@ def load_library():
         lib.span_decode_attn.restype = ctypes.c_int
         lib.dense_decode_attn.argtypes = [DP, P, P, P, P, F, P]
         lib.dense_decode_attn.restype = ctypes.c_int
+        lib.span_decode_attn_append.argtypes = [DP, P, P, P, P, P, P, P, P, P, F, P]
+        lib.span_decode_attn_append.restype = ctypes.c_int
+        lib.dense_decode_attn_append.argtypes = [DP, P, P, P, P, P, P, P, F, P]
+        lib.dense_decode_attn_append.restype = ctypes.c_int
         lib.span_validate.argtypes = [I32, I32, P, P, P, P, P, P, P]
         lib.span_validate.restype = ctypes.c_int
         lib.span_plan_query.argtypes = [DP, ctypes.POINTER(PlanInfo)]
@@ -305,6 +309,54 @@ def prepare_dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out=None, *,
             out.data_ptr())
     return PreparedCall("dense_decode_attn", lib.dense_decode_attn, desc, args, out,
                         (q, k_cache, v_cache, ctx_lens, workspace))
+
+
+def _check_new_rows(q, k_new, v_new):
+    for t, name in ((k_new, "k_new"), (v_new, "v_new")):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != q.dtype or tuple(t.shape) != tuple(q.shape):
+            raise ValueError(f"{name} must be a contiguous GPU tensor shaped and typed like q")
+
+
+def prepare_span_decode_attn_append(q, k_new, v_new, k_cache, v_cache, append_pos, span_offsets, span_starts,
+                                    span_ends, scale, out=None, *, max_tokens=0, num_splits=0, workspace=None,
+                                    stream=None, tokens_per_seq=None) -> PreparedCall:
+    lib = load_library()
+    n_int = int(span_starts.numel())
+    desc, out, workspace = _prepare(q, k_cache, v_cache, out, n_int, max_tokens, num_splits, workspace, stream,
+                                    tokens_per_seq)
+    _check_new_rows(q, k_new, v_new)
+    args = (ctypes.byref(desc), q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), k_cache.data_ptr(),
+            v_cache.data_ptr(), _i32_dev(append_pos, desc.batch, "append_pos"),
+            _i32_dev(span_offsets, desc.batch + 1, "span_offsets"), _i32_dev(span_starts, n_int, "span_starts"),
+            _i32_dev(span_ends, n_int, "span_ends"), float(scale), out.data_ptr())
+    keep = (q, k_new, v_new, k_cache, v_cache, append_pos, span_offsets, span_starts, span_ends, workspace)
+    return PreparedCall("span_decode_attn_append", lib.span_decode_attn_append, desc, args, out, keep)
+
+
+def prepare_dense_decode_attn_append(q, k_new, v_new, k_cache, v_cache, append_pos, ctx_lens, scale, out=None, *,
+                                     max_tokens=0, num_splits=0, workspace=None, stream=None,
+                                     tokens_per_seq=None) -> PreparedCall:
+    lib = load_library()
+    desc, out, workspace = _prepare(q, k_cache, v_cache, out, 0, max_tokens, num_splits, workspace, stream,
+                                    tokens_per_seq)
+    _check_new_rows(q, k_new, v_new)
+    args = (ctypes.byref(desc), q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), k_cache.data_ptr(),
+            v_cache.data_ptr(), _i32_dev(append_pos, desc.batch, "append_pos"),
+            _i32_dev(ctx_lens, desc.batch, "ctx_lens"), float(scale), out.data_ptr())
+    keep = (q, k_new, v_new, k_cache, v_cache, append_pos, ctx_lens, workspace)
+    return PreparedCall("dense_decode_attn_append", lib.dense_decode_attn_append, desc, args, out, keep)
+
+
+def span_decode_attn_append(q, k_new, v_new, k_cache, v_cache, append_pos, span_offsets, span_starts, span_ends,
+                            scale, out=None, **kw):
+    """Writes the new token's K / V rows into the caches at append_pos[b] and attends over the updated cache."""
+    return prepare_span_decode_attn_append(q, k_new, v_new, k_cache, v_cache, append_pos, span_offsets, span_starts,
+                                           span_ends, scale, out, **kw)()
+
+
+def dense_decode_attn_append(q, k_new, v_new, k_cache, v_cache, append_pos, ctx_lens, scale, out=None, **kw):
+    return prepare_dense_decode_attn_append(q, k_new, v_new, k_cache, v_cache, append_pos, ctx_lens, scale, out,
+                                            **kw)()
 
 
 def span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out=None, *,

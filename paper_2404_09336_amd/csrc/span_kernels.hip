@@ -49,6 +49,9 @@ struct LaunchArgs {
   const int32_t* starts;
   const int32_t* ends;
   const int32_t* ctx_lens;
+  const void* k_new;           // append variant: the new token's K / V rows [batch, heads, D], else null
+  const void* v_new;
+  const int32_t* append_pos;   // append variant: [batch] cache row that receives them
   int32_t* counters;  // [batch*heads] arrival tickets of the slices; zero between calls
   float* part_ml;   // [batch*heads, num_splits, 2]  (m in log2 units, l)
   float* part_acc;  // [batch*heads, num_splits, D]  un-normalised
@@ -200,6 +203,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   const int grp = lane / LPR, lir = lane % LPR;
   const size_t bh = (size_t)b * a.heads + h;
 
+  // Append variant: the new token's K / V row is written into the cache here (by the first slice's
+  // workgroup of each (batch, head)) and, in this launch, never read back from the cache: whoever meets
+  // position new_pos takes the row from k_new / v_new instead, so there is no race inside the kernel.
+  const int new_pos = a.append_pos ? a.append_pos[b] : -2;  // -2 matches no position
+  if (a.append_pos && split == 0 && new_pos >= 0 && new_pos < a.max_len && tid < 2 * LPR) {
+    const bool is_v = tid >= LPR;
+    const char* src = (const char*)(is_v ? a.v_new : a.k_new) + bh * ROWB + (uint32_t)(tid % LPR) * 16u;
+    char* dst = (char*)(is_v ? a.v : a.k) + (bh * (size_t)a.max_len + (size_t)new_pos) * ROWB + (uint32_t)(tid % LPR) * 16u;
+    *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(src);
+  }
+
   __shared__ int s_pos[kWavesPerBlock][kRowsPerWaveMax];
   __shared__ int s_pref[kWavesPerBlock][64];
   __shared__ int s_start[kWavesPerBlock][64];
@@ -331,6 +345,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   float acc[EPL];
 #pragma unroll
   for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+  bool met_new = false;  // my row group owns the appended row
 
   for (int base = 0; base < nrows; base += RPL * U) {
     u32x4 kr[U], vr[U];
@@ -341,7 +356,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
       ok[u] = r < nrows;
       const int rc = ok[u] ? r : nrows - 1;  // a row past the end re-reads the last one with weight 0
       const int p = kDense ? vrow(rc) : s_pos[wave][rc];
-      const uint32_t off = (uint32_t)p * ROWB + lane_off;
+      // the appended row is not in the cache yet for this launch: request an offset past the slab
+      // (the buffer hardware returns zeros) and give it no weight here; it is added after the loop
+      const bool is_new = p == new_pos;
+      met_new = met_new || (is_new && ok[u]);
+      ok[u] = ok[u] && !is_new;
+      const uint32_t off = is_new ? 0xfffffff0u : (uint32_t)p * ROWB + lane_off;
       kr[u] = load_row_piece(kslab, off);
       vr[u] = load_row_piece(vslab, off);
     }
@@ -373,6 +393,25 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
 #pragma unroll
       for (int i = 0; i < EPL; ++i) acc[i] = fmaf(p, vf[i], acc[i]);
     }
+    m = m_new;
+  }
+
+  if (__builtin_amdgcn_ballot_w64(met_new) != 0) {  // (wave-uniform) some row group here owns the appended row
+    const uint32_t piece = (uint32_t)(bh * ROWB) + lane_off;
+    float kf[EPL], vf[EPL];
+    Elt::unpack(*reinterpret_cast<const u32x4*>((const char*)a.k_new + piece), kf);
+    Elt::unpack(*reinterpret_cast<const u32x4*>((const char*)a.v_new + piece), vf);
+    float d = 0.f;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[i], d);
+    d = group_allreduce_sum<LPR>(d);
+    const float s_new = met_new ? d : -INFINITY;
+    const float m_new = fmaxf(m, s_new);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m - m_safe), p = __builtin_amdgcn_exp2f(s_new - m_safe);
+    l = l * alpha + p;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] = fmaf(p, vf[i], acc[i] * alpha);
     m = m_new;
   }
 
@@ -488,7 +527,8 @@ int launch_typed(const LaunchArgsTable& a, bool use_table, int batch, hipStream_
 
 template <bool kDense>
 int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* v, const int32_t* offsets,
-           const int32_t* starts, const int32_t* ends, const int32_t* ctx_lens, float scale, float* out) {
+           const int32_t* starts, const int32_t* ends, const int32_t* ctx_lens, float scale, float* out,
+           const void* k_new = nullptr, const void* v_new = nullptr, const int32_t* append_pos = nullptr) {
   const int rc = check_desc(d);
   if (rc != SPAN_OK) return rc;
   if (!q || !k || !v || !out) return SPAN_ERR_NULL;
@@ -507,6 +547,9 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   a.starts = starts;
   a.ends = ends;
   a.ctx_lens = ctx_lens;
+  a.k_new = k_new;
+  a.v_new = v_new;
+  a.append_pos = append_pos;
   a.counters = need ? (int32_t*)d->workspace : nullptr;
   a.part_ml = need ? (float*)((char*)d->workspace + workspace_counter_bytes(d)) : nullptr;
   a.part_acc = need ? (float*)((char*)d->workspace + workspace_counter_bytes(d) + workspace_ml_bytes(d, p)) : nullptr;
@@ -546,6 +589,23 @@ extern "C" int span_decode_attn(const span_attn_desc_t* desc, const void* q, con
 extern "C" int dense_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_cache,
                                  const void* v_cache, const int32_t* ctx_lens, float scale, float* out) {
   return spanattn::launch<true>(desc, q, k_cache, v_cache, nullptr, nullptr, nullptr, ctx_lens, scale, out);
+}
+
+extern "C" int span_decode_attn_append(const span_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                                       void* k_cache, void* v_cache, const int32_t* append_pos,
+                                       const int32_t* span_offsets, const int32_t* span_starts,
+                                       const int32_t* span_ends, float scale, float* out) {
+  if (!k_new || !v_new || !append_pos) return SPAN_ERR_NULL;
+  return spanattn::launch<false>(desc, q, k_cache, v_cache, span_offsets, span_starts, span_ends, nullptr, scale, out,
+                                 k_new, v_new, append_pos);
+}
+
+extern "C" int dense_decode_attn_append(const span_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                                        void* k_cache, void* v_cache, const int32_t* append_pos,
+                                        const int32_t* ctx_lens, float scale, float* out) {
+  if (!k_new || !v_new || !append_pos) return SPAN_ERR_NULL;
+  return spanattn::launch<true>(desc, q, k_cache, v_cache, nullptr, nullptr, nullptr, ctx_lens, scale, out, k_new,
+                                v_new, append_pos);
 }
 
 extern "C" int span_workspace_init(const span_attn_desc_t* desc) {

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"span_decode_attn", "dense_decode_attn", "span_validate", "span_plan_query", "span_workspace_bytes",
             "span_workspace_init", "span_strerror", "span_last_hip_error", "span_blocks_to_intervals",
-            "span_intervals_to_blocks", "span_build"} <= set(names)
+            "span_intervals_to_blocks", "span_build", "span_decode_attn_append", "dense_decode_attn_append"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 

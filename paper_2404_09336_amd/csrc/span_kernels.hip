@@ -203,15 +203,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   const int grp = lane / LPR, lir = lane % LPR;
   const size_t bh = (size_t)b * a.heads + h;
 
-  // Append variant: the new token's K / V row is written into the cache here (by the first slice's
-  // workgroup of each (batch, head)) and, in this launch, never read back from the cache: whoever meets
-  // position new_pos takes the row from k_new / v_new instead, so there is no race inside the kernel.
+  // Append variant.  Every lane fetches its piece of the new token's K / V row right away (the latency
+  // hides behind the metadata chain).  The row is written into the cache by the first slice's workgroup
+  // of each (batch, head) and, in this launch, never read back from the cache: the wave that meets
+  // position new_pos in its rows takes it from these registers instead, so the kernel has no race.
   const int new_pos = a.append_pos ? a.append_pos[b] : -2;  // -2 matches no position
-  if (a.append_pos && split == 0 && new_pos >= 0 && new_pos < a.max_len && tid < 2 * LPR) {
-    const bool is_v = tid >= LPR;
-    const char* src = (const char*)(is_v ? a.v_new : a.k_new) + bh * ROWB + (uint32_t)(tid % LPR) * 16u;
-    char* dst = (char*)(is_v ? a.v : a.k) + (bh * (size_t)a.max_len + (size_t)new_pos) * ROWB + (uint32_t)(tid % LPR) * 16u;
-    *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(src);
+  u32x4 kn_raw = {0u, 0u, 0u, 0u}, vn_raw = {0u, 0u, 0u, 0u};
+  if (a.append_pos) {
+    kn_raw = *reinterpret_cast<const u32x4*>((const char*)a.k_new + bh * ROWB + (uint32_t)lir * 16u);
+    vn_raw = *reinterpret_cast<const u32x4*>((const char*)a.v_new + bh * ROWB + (uint32_t)lir * 16u);
   }
 
   __shared__ int s_pos[kWavesPerBlock][kRowsPerWaveMax];
@@ -345,8 +345,31 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   float acc[EPL];
 #pragma unroll
   for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
-  bool met_new = false;  // my row group owns the appended row
 
+  if (a.append_pos) {
+    if (split == 0 && wave == 0 && lane < LPR && new_pos >= 0 && new_pos < a.max_len) {  // the cache write
+      const size_t row = (bh * (size_t)a.max_len + (size_t)new_pos) * ROWB + lane_off;
+      *reinterpret_cast<u32x4*>((char*)a.k + row) = kn_raw;
+      *reinterpret_cast<u32x4*>((char*)a.v + row) = vn_raw;
+    }
+    bool mine = false;  // is the appended row one of my rows?
+    for (int r = lane; r < nrows; r += 64) mine = mine || (kDense ? vrow(r) : s_pos[wave][r]) == new_pos;
+    if (__builtin_amdgcn_ballot_w64(mine) != 0) {  // wave-uniform: row group 0 starts from the new row
+      float kf[EPL], vf[EPL];
+      Elt::unpack(kn_raw, kf);
+      Elt::unpack(vn_raw, vf);
+      float d = 0.f;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[i], d);
+      d = group_allreduce_sum<LPR>(d);
+      if (grp == 0) {
+        m = d;
+        l = 1.f;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[i] = vf[i];
+      }
+    }
+  }
   for (int base = 0; base < nrows; base += RPL * U) {
     u32x4 kr[U], vr[U];
     bool ok[U];
@@ -359,7 +382,6 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
       // the appended row is not in the cache yet for this launch: request an offset past the slab
       // (the buffer hardware returns zeros) and give it no weight here; it is added after the loop
       const bool is_new = p == new_pos;
-      met_new = met_new || (is_new && ok[u]);
       ok[u] = ok[u] && !is_new;
       const uint32_t off = is_new ? 0xfffffff0u : (uint32_t)p * ROWB + lane_off;
       kr[u] = load_row_piece(kslab, off);
@@ -393,25 +415,6 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
 #pragma unroll
       for (int i = 0; i < EPL; ++i) acc[i] = fmaf(p, vf[i], acc[i]);
     }
-    m = m_new;
-  }
-
-  if (__builtin_amdgcn_ballot_w64(met_new) != 0) {  // (wave-uniform) some row group here owns the appended row
-    const uint32_t piece = (uint32_t)(bh * ROWB) + lane_off;
-    float kf[EPL], vf[EPL];
-    Elt::unpack(*reinterpret_cast<const u32x4*>((const char*)a.k_new + piece), kf);
-    Elt::unpack(*reinterpret_cast<const u32x4*>((const char*)a.v_new + piece), vf);
-    float d = 0.f;
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[i], d);
-    d = group_allreduce_sum<LPR>(d);
-    const float s_new = met_new ? d : -INFINITY;
-    const float m_new = fmaxf(m, s_new);
-    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m - m_safe), p = __builtin_amdgcn_exp2f(s_new - m_safe);
-    l = l * alpha + p;
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) acc[i] = fmaf(p, vf[i], acc[i] * alpha);
     m = m_new;
   }
 
@@ -500,7 +503,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
       merge_state(mm, ll, &oo, 1, s_gm[j][t], s_gl[j][t], &o2);
     }
     a.out[bh * D + t] = ll > 0.f ? oo / ll : 0.f;
-    if (tid == 0) a.counters[bh] = 0;  // leave the ticket counter ready for the next call
+    // leave the ticket counter ready for the next call (same device-coherent access path as the tickets)
+    if (tid == 0) __hip_atomic_store(&a.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 

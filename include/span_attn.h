@@ -160,7 +160,7 @@ typedef struct span_plan_info {
                               sequence gets max_splits slices of slice_tokens positions            */
   int32_t slice_tokens;    /* attended positions per slice (upper bound in exact mode)            */
   int32_t max_splits;      /* most slices any (batch, head) pair is cut into                      */
-  int32_t reserved;
+  int32_t slice_limit;     /* most positions one slice can own (a constant of the build)                */
   int64_t workgroups;      /* workgroups the call launches                                        */
   int64_t workspace_bytes; /* same value as span_workspace_bytes()                                */
 } span_plan_info_t;

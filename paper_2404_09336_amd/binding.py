@@ -31,11 +31,11 @@ class _Desc(ctypes.Structure):
 
 class PlanInfo(ctypes.Structure):
     _fields_ = [("exact", ctypes.c_int32), ("slice_tokens", ctypes.c_int32), ("max_splits", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("workgroups", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
+                ("slice_limit", ctypes.c_int32), ("workgroups", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
 
     def as_dict(self):
         return {"exact": bool(self.exact), "slice_tokens": self.slice_tokens, "max_splits": self.max_splits,
-                "workgroups": self.workgroups, "workspace_bytes": self.workspace_bytes}
+                "slice_limit": self.slice_limit, "workgroups": self.workgroups, "workspace_bytes": self.workspace_bytes}
 
 
 def lib_path() -> str:

@@ -65,11 +65,10 @@ static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 //
 // All workgroups of a launch that fit on the chip at once start together and spend the same first
 // microseconds walking the span metadata before any K row is requested; a second round of equal
-// workgroups would repeat that dead time.  So the aim is ONE resident round: the smallest slice size T
-// for which all slices of all sequences, times heads, fit into kTargetWorkgroups.  Sequence b gets
-// ceil(n_b / T) slices, which the kernel makes equal-sized.  Only when even the largest slice the
-// kernel supports does not fit (more work than one round can hold) do the slices stop growing:
-// kMultiRoundSlice then gives enough workgroups for the rounds to drift apart and balance the tail.
+// workgroups would repeat that dead time, and every extra slice costs a partial state and a ticket.
+// So the aim is ONE resident round: the smallest slice size T for which all slices of all sequences,
+// times heads, fit into kTargetWorkgroups.  Sequence b gets ceil(n_b / T) slices, which the kernel makes
+// equal-sized.  When batch * heads alone exceeds a round, every sequence is one slice.
 static int64_t slices_for(int64_t n, int64_t T) { return n <= 0 ? 1 : ceil_div(n, T); }
 
 static bool plan_exact(const span_attn_desc_t* d, int64_t max_tok, Partition* p, uint32_t* table) {
@@ -85,43 +84,43 @@ static bool plan_exact(const span_attn_desc_t* d, int64_t max_tok, Partition* p,
   };
   int64_t sum = 0;
   for (int32_t b = 0; b < d->batch; ++b) sum += tokens(b);
-  const int64_t room = kTargetWorkgroups / d->heads;  // slices (per head) that fit in one round
+  int64_t room = kTargetWorkgroups / d->heads;  // slices (per head) that fit in one round
+  if (room > kMaxPlanSlices) room = kMaxPlanSlices;
   int64_t T = ceil_div(sum * d->heads, kTargetWorkgroups);
   if (T < kMinSlice) T = kMinSlice;
-  int64_t total = 0;
-  for (;;) {
-    if (T >= kMaxSlice) {  // more than one round whatever we do
-      T = room >= d->batch && count(kMaxSlice) <= room ? kMaxSlice : kMultiRoundSlice;
-      total = count(T);
-      break;
-    }
+  int64_t total = count(T);
+  if (room < d->batch) {  // batch * heads alone exceeds a round: whole sequences
+    T = max_tok > 0 ? max_tok : 1;
     total = count(T);
-    if (room < d->batch) break;
-    if (total <= room) {  // fits: give back what the proportional step overshot
-      for (int i = 0; i < 8 && T - kSliceGranule >= kMinSlice && count(T - kSliceGranule) <= room; ++i)
-        T -= kSliceGranule;
+  } else {
+    while (total > room) {  // grow T in proportion to the overshoot (at least one granule) and try again
+      const int64_t next = ceil_div(ceil_div(T * total, room), kSliceGranule) * kSliceGranule;
+      T = next > T ? next : T + kSliceGranule;
       total = count(T);
-      break;
     }
-    // grow T in proportion to the overshoot (at least one granule) and try again
-    int64_t next = ceil_div(ceil_div(T * total, room), kSliceGranule) * kSliceGranule;
-    T = next > T ? next : T + kSliceGranule;
-  }
-  if (room < d->batch) {  // batch * heads alone exceeds a round: one slice per sequence where possible
-    T = kMaxSlice;
+    // fits: give back what the proportional step overshot
+    for (int i = 0; i < 8 && T - kSliceGranule >= kMinSlice && count(T - kSliceGranule) <= room; ++i)
+      T -= kSliceGranule;
     total = count(T);
   }
-  if (total > kMaxPlanSlices) return false;
   int64_t most = 1, least = kMaxPlanSplits + 1, largest = 1;
-  int32_t y = 0;
   for (int32_t b = 0; b < d->batch; ++b) {
     const int64_t n = tokens(b), nsl = slices_for(n, T);
-    if (nsl > kMaxPlanSplits) return false;
     if (nsl > most) most = nsl;
     if (nsl < least) least = nsl;
     if (ceil_div(n, nsl) > largest) largest = ceil_div(n, nsl);
-    if (table)
-      for (int64_t s = 0; s < nsl; ++s) table[y++] = pack_slice((uint32_t)b, (uint32_t)s, (uint32_t)nsl);
+  }
+  if (most != least) {  // sequences differ in their number of slices: the table is needed, and must fit
+    if (total > kMaxPlanSlices || most > kMaxPlanSplits) return false;
+    if (table) {
+      int32_t y = 0;
+      for (int32_t b = 0; b < d->batch; ++b) {
+        const int64_t nsl = slices_for(tokens(b), T);
+        for (int64_t s = 0; s < nsl; ++s) table[y++] = pack_slice((uint32_t)b, (uint32_t)s, (uint32_t)nsl);
+      }
+    }
+  } else if (most > 65535) {
+    return false;  // grid.y limit of the plain grid
   }
   p->exact = most != least;  // same count for every sequence: a (heads, slices, batch) grid says it all
   p->even = true;
@@ -184,7 +183,7 @@ extern "C" int span_plan_query(const span_attn_desc_t* desc, span_plan_info_t* i
   info->exact = p.even ? 1 : 0;
   info->slice_tokens = p.slice_tokens;
   info->max_splits = p.num_splits;
-  info->reserved = 0;
+  info->slice_limit = spanattn::kMaxSlice;
   info->workgroups = (int64_t)p.total_slices * desc->heads;
   info->workspace_bytes = (int64_t)spanattn::workspace_bytes(desc, p);
   return SPAN_OK;

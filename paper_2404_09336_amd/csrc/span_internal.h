@@ -10,14 +10,13 @@
 namespace spanattn {
 
 constexpr int kWavesPerBlock = 4;          // 256 threads per workgroup
-constexpr int kMaxSlice = 1024;            // attended positions one workgroup can own (LDS position table)
+constexpr int kMaxSlice = 1 << 22;         // a slice may be a whole sequence (positions are tabulated window by window)
 constexpr int kMinSlice = 64;              // do not cut work finer than this many positions
 constexpr int kSliceGranule = 16;
 constexpr int kMaxLen = 1 << 22;           // keeps every in-slab byte offset inside 32 bits
 constexpr int64_t kTargetWorkgroups = 2048;  // 256 CUs x 8 resident workgroups
 
 constexpr int kInterleaveFrom = 384;        // slices at least this large deal their rows to the waves round-robin
-constexpr int kMultiRoundSlice = 1024;       // slice size once there is more work than one resident round holds
 constexpr int kMaxPlanSlices = 768;        // entries of the slice table passed as kernel argument
 constexpr int kMaxPlanBatch = 1024;        // 10 bits of a table entry
 constexpr int kMaxPlanSplits = 2047;       // 11 bits of a table entry

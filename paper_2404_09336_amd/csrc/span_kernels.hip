@@ -28,6 +28,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "span_attn.h"
 #include "span_internal.h"
 
@@ -38,7 +40,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = kWavesPerBlock * 64;
-constexpr int kRowsPerWaveMax = kMaxSlice / kWavesPerBlock;
+constexpr int kWin = 256;  // rows of a wave whose positions are tabulated at a time (one LDS window)
 
 struct LaunchArgs {
   const void* q;
@@ -199,7 +201,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
     nsl = a.num_splits;
     y0 = b * nsl;
   }
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: what derives from it stays scalar
   const int grp = lane / LPR, lir = lane % LPR;
   const size_t bh = (size_t)b * a.heads + h;
 
@@ -214,7 +217,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
     vn_raw = *reinterpret_cast<const u32x4*>((const char*)a.v_new + bh * ROWB + (uint32_t)lir * 16u);
   }
 
-  __shared__ int s_pos[kWavesPerBlock][kRowsPerWaveMax];
+  __shared__ int s_pos[kWavesPerBlock][kWin];
+  __shared__ u32x4 s_new[kWavesPerBlock][2][LPR];  // append variant: the new K / V row, parked until its owner needs it
   __shared__ int s_pref[kWavesPerBlock][64];
   __shared__ int s_start[kWavesPerBlock][64];
   __shared__ float s_acc[kWavesPerBlock][D];
@@ -257,7 +261,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
     }
   }
   n_total = n_total < a.max_tokens ? n_total : a.max_tokens;
-  const int T = a.even ? min((n_total + nsl - 1) / nsl, kMaxSlice) : a.slice_tokens;
+  const int T = a.even ? (n_total + nsl - 1) / nsl : a.slice_tokens;
   const int slice_begin = split * T;
   const int cnt = __builtin_amdgcn_readfirstlane(clampi(n_total - slice_begin, 0, T));
 
@@ -288,15 +292,43 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
     return slice_begin + (a.interleave ? ((r / RPL) * kWavesPerBlock + wave) * RPL + (r % RPL) : q_first + r);
   };
 
-  // ---- step 2: virtual token -> KV position for my rows (span path only) -----------------------
-  if (!kDense && nrows > 0) {
-    const int vbeg = vrow(0), vend = vrow(nrows - 1) + 1;
+  // ---- steps 2 and 3, one window of kWin rows at a time -----------------------------------------
+  const uint32_t slab_bytes = (uint32_t)a.max_len * ROWB;
+  const __amdgpu_buffer_rsrc_t kslab = slab_resource((const char*)a.k + bh * (size_t)slab_bytes, slab_bytes);
+  const __amdgpu_buffer_rsrc_t vslab = slab_resource((const char*)a.v + bh * (size_t)slab_bytes, slab_bytes);
+  const uint32_t lane_off = (uint32_t)lir * 16u;
+
+  float m = -INFINITY, l = 0.f;
+  float acc[EPL];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+
+  if (a.append_pos) {
+    if (lane < LPR) {  // park the new row in LDS (frees the registers); the first slice also writes the cache
+      s_new[wave][0][lane] = kn_raw;
+      s_new[wave][1][lane] = vn_raw;
+      if (split == 0 && wave == 0 && new_pos >= 0 && new_pos < a.max_len) {
+        const size_t row = (bh * (size_t)a.max_len + (size_t)new_pos) * ROWB + lane_off;
+        *reinterpret_cast<u32x4*>((char*)a.k + row) = kn_raw;
+        *reinterpret_cast<u32x4*>((char*)a.v + row) = vn_raw;
+      }
+    }
+  }
+
+  // ---- step 2: virtual token -> KV position for a window's rows (span path only) -----------------
+  // kFirst: the first 64 intervals are still in registers from step 1; later windows (slices of more
+  // than kWin rows per wave) re-read them, so that nothing from step 1 stays live across the streaming loop.
+  auto tabulate = [&](auto first_tag, int w0, int wn) {
+    constexpr bool kFirst = decltype(first_tag)::value;
+    const int vbeg = vrow(w0), vend = vrow(w0 + wn - 1) + 1;
     int carry = 0;
     for (int c0 = 0; c0 < n_int; c0 += 64) {
-      int st = st0, len = len0, incl = incl0;
-      if (c0 > 0) {
-        st = 0;
-        len = 0;
+      int st = 0, len = 0, incl = 0;
+      if (kFirst && c0 == 0) {
+        st = st0;
+        len = len0;
+        incl = incl0;
+      } else {
         if (c0 + lane < n_int) {
           st = a.starts[off0 + c0 + lane];
           len = clampi(a.ends[off0 + c0 + lane] - st, 0, a.max_len);
@@ -313,8 +345,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const int n_here = min(64, n_int - c0);
-        for (int r = lane; r < nrows; r += 64) {
-          const int v = vrow(r);
+        for (int r = lane; r < wn; r += 64) {
+          const int v = vrow(w0 + r);
           if (v >= carry && v < carry + chunk_total) {
             int idx = 0;  // last interval of the chunk whose exclusive prefix is <= v
 #pragma unroll
@@ -333,54 +365,43 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
       carry += chunk_total;
       if (carry >= vend) break;
     }
-  }
+  };
+  if (!kDense && nrows > 0) tabulate(std::true_type{}, 0, min(kWin, nrows));
 
-  // ---- step 3: stream my K and V rows, online softmax per row group ----------------------------
-  const uint32_t slab_bytes = (uint32_t)a.max_len * ROWB;
-  const __amdgpu_buffer_rsrc_t kslab = slab_resource((const char*)a.k + bh * (size_t)slab_bytes, slab_bytes);
-  const __amdgpu_buffer_rsrc_t vslab = slab_resource((const char*)a.v + bh * (size_t)slab_bytes, slab_bytes);
-  const uint32_t lane_off = (uint32_t)lir * 16u;
+  for (int w0 = 0; w0 < nrows; w0 += kWin) {
+  const int wn = min(kWin, nrows - w0);  // rows w0 .. w0+wn-1 of mine
+  if (!kDense && w0 > 0) tabulate(std::false_type{}, w0, wn);
 
-  float m = -INFINITY, l = 0.f;
-  float acc[EPL];
-#pragma unroll
-  for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
-
-  if (a.append_pos) {
-    if (split == 0 && wave == 0 && lane < LPR && new_pos >= 0 && new_pos < a.max_len) {  // the cache write
-      const size_t row = (bh * (size_t)a.max_len + (size_t)new_pos) * ROWB + lane_off;
-      *reinterpret_cast<u32x4*>((char*)a.k + row) = kn_raw;
-      *reinterpret_cast<u32x4*>((char*)a.v + row) = vn_raw;
-    }
-    bool mine = false;  // is the appended row one of my rows?
-    for (int r = lane; r < nrows; r += 64) mine = mine || (kDense ? vrow(r) : s_pos[wave][r]) == new_pos;
-    if (__builtin_amdgcn_ballot_w64(mine) != 0) {  // wave-uniform: row group 0 starts from the new row
+  if (a.append_pos) {  // is the appended row one of the window's rows?  Then row group 0 takes it in now.
+    bool mine = false;
+    for (int r = lane; r < wn; r += 64) mine = mine || (kDense ? vrow(w0 + r) : s_pos[wave][r]) == new_pos;
+    if (__builtin_amdgcn_ballot_w64(mine) != 0) {  // wave-uniform
       float kf[EPL], vf[EPL];
-      Elt::unpack(kn_raw, kf);
-      Elt::unpack(vn_raw, vf);
+      Elt::unpack(s_new[wave][0][lir], kf);
+      Elt::unpack(s_new[wave][1][lir], vf);
       float d = 0.f;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[i], d);
       d = group_allreduce_sum<LPR>(d);
       if (grp == 0) {
-        m = d;
-        l = 1.f;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i] = vf[i];
+        const float l_one = 1.f;
+        merge_state(m, l, acc, EPL, d, l_one, vf);
       }
     }
   }
-  for (int base = 0; base < nrows; base += RPL * U) {
+
+  // ---- step 3: stream the window's K and V rows, online softmax per row group -------------------
+  for (int base = 0; base < wn; base += RPL * U) {
     u32x4 kr[U], vr[U];
     bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = base + u * RPL + grp;
-      ok[u] = r < nrows;
-      const int rc = ok[u] ? r : nrows - 1;  // a row past the end re-reads the last one with weight 0
-      const int p = kDense ? vrow(rc) : s_pos[wave][rc];
+      ok[u] = r < wn;
+      const int rc = ok[u] ? r : wn - 1;  // a row past the end re-reads the last one with weight 0
+      const int p = kDense ? vrow(w0 + rc) : s_pos[wave][rc];
       // the appended row is not in the cache yet for this launch: request an offset past the slab
-      // (the buffer hardware returns zeros) and give it no weight here; it is added after the loop
+      // (the buffer hardware returns zeros) and give it no weight here; its owner added it above
       const bool is_new = p == new_pos;
       ok[u] = ok[u] && !is_new;
       const uint32_t off = is_new ? 0xfffffff0u : (uint32_t)p * ROWB + lane_off;
@@ -417,6 +438,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
     }
     m = m_new;
   }
+  }  // windows
 
   // ---- step 4: merge row groups (shuffles), then waves (LDS) ------------------------------------
 #pragma unroll
@@ -512,14 +534,18 @@ thread_local int g_last_hip_error = 0;
 
 template <class Elt, int D, bool kDense>
 int launch_typed(const LaunchArgsTable& a, bool use_table, int batch, hipStream_t stream) {
+  // K loads (and as many V loads) a wave has in flight before it consumes the first: 4 KiB + 4 KiB, but
+  // never more than 16 rows (with 128-byte rows that is 2 instructions of 8 rows)
+  constexpr int kRowsPerLoad = 64 / (D / Elt::kPerVec);
+  constexpr int kInFlight = kRowsPerLoad >= 8 ? 2 : 4;
   if (use_table) {
     const dim3 grid((unsigned)a.heads, (unsigned)a.total_slices, 1u);
-    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, 4, LaunchArgsTable>), grid, dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, LaunchArgsTable>), grid, dim3(kThreads), 0, stream, a);
   } else {
     const dim3 grid((unsigned)a.heads, (unsigned)a.num_splits, (unsigned)batch);
     LaunchArgsPlain plain;
     static_cast<LaunchArgs&>(plain) = static_cast<const LaunchArgs&>(a);
-    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, 4, LaunchArgsPlain>), grid, dim3(kThreads), 0, stream, plain);
+    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, LaunchArgsPlain>), grid, dim3(kThreads), 0, stream, plain);
   }
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) {

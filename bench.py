@@ -210,7 +210,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus must be 1. The path shards over batch "
-              "or heads with no collective (see DESIGN.md), but no multi-GPU run exists here.", file=sys.stderr)
+              "or heads with no collective, but no multi-GPU run exists here.", file=sys.stderr)
         sys.exit(2)
     import torch
     import paper_2404_09336_amd as span

@@ -96,7 +96,8 @@ def auto_copies(cfg_id):
     touched = int(sp.tokens_per_seq().sum()) * 2 * cfg.head_dim * cfg.elt_bytes * cfg.heads
     alloc = 2 * cfg.batch * cfg.heads * cfg.max_len * cfg.head_dim * cfg.elt_bytes
     n = int(np.ceil(2 * LLC_BYTES / max(touched, 1)))
-    n = max(1, min(n, 16, max(1, (32 << 30) // alloc)))
+    n = max(2, n)                                   # always alternate buffers, even when one call exceeds the cache
+    n = max(1, min(n, 16, max(1, (48 << 30) // alloc)))
     return n
 
 

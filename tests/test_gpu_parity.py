@@ -319,3 +319,35 @@ def test_non_default_stream(gpu_device):
     with torch.cuda.stream(s):
         got = run_span(cfg, sp, q, K, V, gpu_device, num_splits=3)
     check(got, ref, cfg.tol, "side stream")
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_shapes_and_lists(seed, gpu_device):
+    """Random batch shapes, list structures and slicing modes; the case is printed before it runs."""
+    from workloads import place_disjoint
+    rng = np.random.default_rng(1000 + seed)
+    dtype = ["f16", "bf16", "f32"][seed % 3]
+    D = [128, 64][(seed // 3) % 2]
+    B = int(rng.integers(1, 7))
+    H = int(rng.choice([1, 3, 8, 32]))
+    L = int(rng.choice([33, 257, 1500, 6000]))
+    cfg = DecodeConfig(200 + seed, "random", B, H, D, L, L, dtype, TOL[dtype])
+    ctx = rng.integers(1, L + 1, size=B).astype(np.int32)
+    per_seq = []
+    for b in range(B):
+        n = int(ctx[b])
+        k = int(rng.integers(1, min(n, 90) + 1))
+        style = rng.integers(0, 3)
+        hi = 1 if style == 0 else (max(1, n // k) if style == 1 else max(1, min(n // k, 7)))
+        lens = rng.integers(1, hi + 1, size=k)
+        per_seq.append(place_disjoint(rng, lens, 0, n))
+    sp = SpanBatch.from_lists(per_seq, ctx)
+    mode = seed % 4
+    kw = [dict(), dict(tokens_per_seq=None), dict(num_splits=int(rng.integers(1, 9))), dict(tokens_per_seq=None, max_tokens=0)][mode]
+    print(f"[case] seed {seed}: {dtype} D={D} B={B} H={H} L={L} ctx={ctx.tolist()} intervals={[len(p) for p in per_seq]} "
+          f"tokens={sp.tokens_per_seq().tolist()} kw={kw}", flush=True)
+    q, K, V = draw_qkv(cfg, ctx, device=gpu_device, seed=seed)
+    check(run_span(cfg, sp, q, K, V, gpu_device, **kw), oracle_span(cfg, sp, q, K, V), cfg.tol, f"random case {seed} span")
+    dkw = {k: v for k, v in kw.items() if k != "max_tokens"}
+    check(run_dense(cfg, ctx, q, K, V, gpu_device, **dkw), oracle_dense(cfg, ctx, q, K, V), cfg.tol,
+          f"random case {seed} dense")

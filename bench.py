@@ -190,8 +190,8 @@ def microbench(device, steps, warmup):
     geo["all"] = round(float(np.exp(np.mean([x for v in logsum.values() for x in v]))), 3)
     return {"metric": "speedup of 50%-sparse span attention over dense decode (kernel micro-benchmark)",
             "unit": "x", "value": geo["all"], "geomean_by_sparsity_block": geo, "rows": rows, "n_gpus": 1,
-            "dtype": "f16 inputs, fp32 accumulate", "data": "synthetic",
-            "config": {"workload": "batch 64, 32 heads x 128, 1 query token, 1024/2048/4096/8096 cached tokens, "
+            "dtype": "f32", "data": "synthetic",
+            "config": {"storage_dtype": "f16", "workload": "batch 64, 32 heads x 128, 1 query token, 1024/2048/4096/8096 cached tokens, "
                                    "50 % kept in runs of 32/64/128/256, masks via 256-token blocked encoding"},
             "paper_context": PAPER_MICROBENCH}
 
@@ -260,9 +260,10 @@ def main():
         "ms_per_step": round(main_res["us_per_call_wall"] * 1e-3, 6),
         "calls_per_s": round(1e6 / main_res["us_per_call_wall"], 1),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.dtype + " inputs, fp32 accumulate", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg.cfg_id} ({cfg.name}): batch {cfg.batch}, {cfg.heads} heads x "
                                f"{cfg.head_dim}, KV length {cfg.min_len}-{cfg.max_len}, 1 query token",
+                   "storage_dtype": cfg.dtype, "arithmetic": "fp32 multiply-accumulate, fp32 softmax, fp32 output",
                    "span_coverage": round(sum(wl.coverages) / len(wl.coverages), 4),
                    "span_bytes_per_call": int(main_res["bytes_per_call"]),
                    "kv_copies_rotated": copies, "plan": wl.plan},

@@ -351,3 +351,30 @@ def test_random_shapes_and_lists(seed, gpu_device):
     dkw = {k: v for k, v in kw.items() if k != "max_tokens"}
     check(run_dense(cfg, ctx, q, K, V, gpu_device, **dkw), oracle_dense(cfg, ctx, q, K, V), cfg.tol,
           f"random case {seed} dense")
+
+
+def test_largest_supported_cache_length(gpu_device):
+    """max_len = 2^22 rows with 512-byte rows (fp32, D=128): a 2 GiB slab per (batch, head), so in-slab byte
+    offsets use all 31 bits; the span touches the first and the very last rows."""
+    L = 1 << 22
+    cfg = DecodeConfig(96, "maxlen", 1, 1, 128, L, L, "f32", 1e-5)
+    g = torch.Generator(device=gpu_device).manual_seed(96)
+    q = torch.randn((1, 1, 128), generator=g, device=gpu_device)
+    K = torch.full((1, 1, L, 128), float("nan"), device=gpu_device)
+    V = torch.full((1, 1, L, 128), float("nan"), device=gpu_device)
+    iv = [(0, 40), (L // 2 - 3, L // 2 + 70), (L - 300, L)]
+    for s, e in iv:
+        K[0, 0, s:e] = torch.randn((e - s, 128), generator=g, device=gpu_device)
+        V[0, 0, s:e] = torch.randn((e - s, 128), generator=g, device=gpu_device)
+    sp = SpanBatch.from_lists([iv], [L])
+    assert span.span_validate(sp.offsets, sp.starts, sp.ends, sp.ctx_lens)[0] == 0
+    hq, hK, hV = q.cpu().numpy(), K.cpu().numpy(), V.cpu().numpy()
+    ref = oracle.span_attn(hq, hK, hV, sp.offsets, sp.starts, sp.ends, np.float32(cfg.scale), dtype="f32")
+    for kw in (dict(), dict(num_splits=3), dict(tokens_per_seq=None, max_tokens=0)):
+        check(run_span(cfg, sp, q, K, V, gpu_device, **kw), ref, cfg.tol, f"max_len 2^22 {kw}")
+    from paper_2404_09336_amd import binding
+    lib = span.load_library()
+    d = binding.make_desc(1, 1, 128, L + 1, 0)
+    assert lib.span_workspace_bytes(d) == 0 and span.span_strerror(-2)        # one row more is refused
+    with pytest.raises(span.SpanAttnError):
+        span.span_plan_query(d)

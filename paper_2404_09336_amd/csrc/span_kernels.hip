@@ -1,4 +1,4 @@
-// Span-restricted single-query (decode) attention for gfx950: kernels and the two C entry points.
+// Span-restricted single-query (decode) attention for gfx950: the kernel and the C entry points that launch it.
 //
 // What is computed: for every (batch b, head h), softmax over the scores of the positions in the
 // sequence's span only, times the matching V rows (paper Sec. 2.1 eqs. (4)-(6) for one query row,
@@ -9,21 +9,25 @@
 // Mapping to the machine (single-query decode is a GEMV: one multiply-add per loaded element, so
 // the kernel is bound by HBM and uses no matrix cores):
 //   * grid = (heads, KV slices, batch).  A sequence's span is flattened into a virtual token index
-//     0..n_b-1 (prefix sums of the interval lengths); slice s owns virtual tokens [s*T, (s+1)*T).
-//     The host picks T so that short spans still give every CU several workgroups.  When the caller
-//     passes the per-sequence token counts, the grid is instead (heads, all slices of all sequences):
-//     a table in the kernel arguments names each slice's sequence, and every sequence is cut into
-//     equal slices of about the same size as everyone else's, so ragged batches leave no idle workgroup.
-//   * a workgroup is 4 wavefronts; each wavefront takes a contiguous quarter of the slice and is
-//     independent of the others until the final merge (it even builds its own part of the
-//     virtual-token -> position table, so no barrier sits in front of the first K load).
-//   * one 64-lane load instruction fetches 1 KiB = whole rows: D*sizeof(elt)/16 lanes per row, each
-//     lane a 128-bit piece.  The q.k dot product is finished with DPP adds inside those lanes; every
-//     row group of a wavefront carries its own online-softmax state (m, l, acc), merged by
+//     0..n_b-1 (prefix sums of the interval lengths) and cut into slices; the host sizes the slices so
+//     that one launch fills the chip about once (2048 workgroups), however large that makes a slice.
+//     When the caller passes the per-sequence token counts, every sequence is cut into equal slices of
+//     about the same size as everyone else's; if the sequences then differ in their number of slices the
+//     grid becomes (heads, all slices of all sequences) and a table in the kernel arguments names each
+//     slice's sequence, so ragged batches leave no idle workgroup.
+//   * a workgroup is 4 wavefronts; each wavefront takes its share of the slice's rows (a contiguous
+//     quarter, or every fourth 1 KiB unit of a large slice) and is independent of the others until the
+//     final merge - it even builds its own part of the virtual-token -> position table (256 rows at a
+//     time), so no barrier sits in front of the first K load.
+//   * one 64-lane buffer load fetches 1 KiB = whole rows: D*sizeof(elt)/16 lanes per row, each lane a
+//     128-bit piece, non-temporal.  The q.k dot product is finished with DPP adds inside those lanes;
+//     every row group of a wavefront carries its own online-softmax state (m, l, acc), merged by
 //     log-sum-exp at the end: first across row groups (shuffles), then across wavefronts (LDS), then
-//     - only if the call uses more than one slice - across slices: every workgroup publishes its
-//     state and takes a ticket; the one that arrives last for its (batch, head) merges them all, so
-//     the whole call is a single launch.
+//     - only if the (batch, head) pair has more than one slice - across slices: every workgroup
+//     publishes its state and takes a ticket; the one that arrives last for its pair merges them all,
+//     so the whole call is a single launch.
+//   * the append entry points also write the new token's K / V row into the cache; within that launch
+//     the row is taken from the arguments, never read back from the cache.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>

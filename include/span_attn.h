@@ -64,7 +64,7 @@ typedef struct span_attn_desc {
                               0 = unknown, use max_len.  Positions beyond it are NOT attended.   */
   int32_t num_splits;      /* 0 = let the library choose; > 0 = requested number of KV slices
                               per (batch, head) (the library may raise it, see
-                              span_plan_splits)                                                  */
+                              span_plan_query)                                                   */
   const int64_t* tokens_per_seq; /* HOST int64 [batch] or NULL: attended positions of every sequence, as
                               span_validate returns them (for the dense call: ctx_lens widened).
                               Lets the library cut the batch into equal-sized slices with no idle
@@ -172,7 +172,7 @@ size_t span_workspace_bytes(const span_attn_desc_t* desc);
 /*
  * Enqueues, on desc->stream, the zeroing of the ticket counters at the head of desc->workspace.
  * Needed once after the workspace is allocated (or after anything else wrote to it), not per call.
- * Uses hipMemsetAsync: do not call it while the stream is being captured into a HIP graph.
+ * The zeroing is a small kernel launch, so the call may also be recorded into a HIP graph.
  */
 int span_workspace_init(const span_attn_desc_t* desc);
 

@@ -6,8 +6,8 @@ package never imports them.
 
 Two independent formulations live here:
   * `span_oracle.c` (plain C, double precision, compiled with gcc): sums over the span's
-    positions only; also the dense control, group states + log-sum-exp merge, and the
-    span-list validator.
+    positions only; also the few-query form (causal limit over the span), the dense
+    control, group states + log-sum-exp merge, and the span-list validator.
   * `bruteforce.py` (numpy float64): additive 0 / -inf mask over *all* positions and a
     full-length softmax, as the mask is defined in Sec. 2.1; small inputs only.
 """
@@ -47,6 +47,7 @@ def _load():
         vp, ip, dp = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
         ci, cf = ctypes.c_int, ctypes.c_float
         lib.oracle_span_attn.argtypes = [ci, ci, ci, ci, ci, vp, vp, vp, ip, ip, ip, cf, dp, ip]
+        lib.oracle_span_attn_multi.argtypes = [ci, ci, ci, ci, ci, ci, vp, vp, vp, ip, ip, ip, ip, cf, dp]
         lib.oracle_dense_attn.argtypes = [ci, ci, ci, ci, ci, vp, vp, vp, ip, cf, dp]
         lib.oracle_span_state.argtypes = [ci, ci, ci, ci, vp, vp, vp, ci, ci, ip, ip, ci, cf, dp, dp, dp]
         lib.oracle_lse_merge.argtypes = [ci, ci, dp, dp, dp, dp]
@@ -91,6 +92,26 @@ def span_attn(q, K, V, offsets, starts, ends, scale, dtype="f32", return_empty=F
                                   _ptr(starts), _ptr(ends), np.float32(scale), _ptr(out), _ptr(empty))
     assert rc == 0
     return (out, empty.astype(bool)) if return_empty else out
+
+
+def span_attn_multi(q, K, V, offsets, starts, ends, q_pos, scale, dtype="f32"):
+    """Few-query form.  q [B,Qn,H,D], K/V [B,H,Lmax,D], q_pos int32 [B] or None -> float64 [B,Qn,H,D];
+    query j of sequence b attends the span positions <= q_pos[b] + j (all of the span when q_pos is None)."""
+    q, K, V = _raw(q, dtype), _raw(K, dtype), _raw(V, dtype)
+    B, H, Lmax, D = K.shape
+    Qn = q.shape[1]
+    assert q.shape == (B, Qn, H, D) and V.shape == K.shape
+    offsets, starts, ends = _i32(offsets), _i32(starts), _i32(ends)
+    assert offsets.shape == (B + 1,)
+    if q_pos is not None:
+        q_pos = _i32(q_pos)
+        assert q_pos.shape == (B,)
+    out = np.zeros((B, Qn, H, D), dtype=np.float64)
+    rc = _load().oracle_span_attn_multi(B, H, D, Lmax, DTYPE_CODES[dtype], Qn, _ptr(q), _ptr(K), _ptr(V),
+                                        _ptr(offsets), _ptr(starts), _ptr(ends),
+                                        _ptr(q_pos) if q_pos is not None else None, np.float32(scale), _ptr(out))
+    assert rc == 0
+    return out
 
 
 def dense_attn(q, K, V, ctx_lens, scale, dtype="f32"):

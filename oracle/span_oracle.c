@@ -125,6 +125,37 @@ int oracle_span_attn(int B, int H, int D, int max_len, int dtype, const void* q,
   return 0;
 }
 
+/*
+ * Few-query form: Qn query rows per sequence, one per consecutive new token, all sharing the sequence's
+ * span.  Query j of sequence b attends the span positions p with p <= q_pos[b] + j: the causal mask of
+ * Sec. 2.1 (a token never attends a later one) laid over the span mask of Sec. 3.3; eqs. (4)-(6) then
+ * apply row by row.  q_pos NULL = no causal limit.  q, out: [B, Qn, H, D].
+ */
+int oracle_span_attn_multi(int B, int H, int D, int max_len, int dtype, int Qn, const void* q, const void* K,
+                           const void* V, const int32_t* offsets, const int32_t* starts, const int32_t* ends,
+                           const int32_t* q_pos, float scale, double* out) {
+  for (int b = 0; b < B; ++b) {
+    int32_t* pos = (int32_t*)malloc(sizeof(int32_t) * (size_t)(max_len > 0 ? max_len : 1));
+    int n = span_positions(starts, ends, offsets[b], offsets[b + 1], max_len, pos);
+    for (int j = 0; j < Qn; ++j) {
+      int nj = n;  /* pos is ascending: the visible positions are a prefix of it */
+      if (q_pos) {
+        int64_t last = (int64_t)q_pos[b] + j;
+        nj = 0;
+        while (nj < n && pos[nj] <= last) ++nj;
+      }
+#pragma omp parallel for schedule(dynamic)
+      for (int h = 0; h < H; ++h) {
+        size_t row = ((size_t)b * Qn + j) * H + h;
+        attend_positions(D, dtype, q, row * D, K, V, ((size_t)b * H + h) * (size_t)max_len * D, pos, nj,
+                         (double)scale, out + row * D);
+      }
+    }
+    free(pos);
+  }
+  return 0;
+}
+
 /* Dense control: S_b = [0, ctx_lens[b]). */
 int oracle_dense_attn(int B, int H, int D, int max_len, int dtype, const void* q, const void* K, const void* V,
                       const int32_t* ctx_lens, float scale, double* out) {

@@ -59,8 +59,9 @@ struct LaunchArgs {
   const void* v_new;
   const int32_t* append_pos;   // append variant: [batch] cache row that receives them
   int32_t* counters;  // [batch*heads] arrival tickets of the slices; zero between calls
-  float* part_ml;   // [batch*heads, num_splits, 2]  (m in log2 units, l)
-  float* part_acc;  // [batch*heads, num_splits, D]  un-normalised
+  // one slot per workgroup, slot = (first slice row of the sequence + slice) * heads + head:
+  float* part_ml;   // [slots, 2]  (m in log2 units, l)
+  float* part_acc;  // [slots, D]  un-normalised
   int32_t heads, max_len, num_intervals, slice_tokens, num_splits, max_tokens;
   float scale_log2e;
   int32_t total_slices;             // table mode: entries of `table` in use
@@ -534,6 +535,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   }
 }
 
+// Zeroes n 32-bit words (a plain kernel, so that the call can also be recorded into a HIP graph).
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
 thread_local int g_last_hip_error = 0;
 
 template <class Elt, int D, bool kDense>
@@ -649,8 +656,10 @@ extern "C" int span_workspace_init(const span_attn_desc_t* desc) {
   const size_t need = spanattn::workspace_bytes(desc, p);
   if (need == 0) return SPAN_OK;
   if (!desc->workspace || ((uintptr_t)desc->workspace & 255u) || desc->workspace_bytes < need) return SPAN_ERR_WORKSPACE;
-  const hipError_t err =
-      hipMemsetAsync(desc->workspace, 0, spanattn::workspace_counter_bytes(desc), (hipStream_t)desc->stream);
+  const size_t words = spanattn::workspace_counter_bytes(desc) / sizeof(uint32_t);
+  hipLaunchKernelGGL(spanattn::zero_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
+                     (hipStream_t)desc->stream, (uint32_t*)desc->workspace, words);
+  const hipError_t err = hipGetLastError();
   if (err != hipSuccess) {
     spanattn::g_last_hip_error = (int)err;
     return SPAN_ERR_HIP;

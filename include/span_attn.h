@@ -79,6 +79,8 @@ typedef struct span_attn_desc {
                               time must not share a workspace.                                  */
   size_t workspace_bytes;
   void* stream;            /* hipStream_t; NULL = the default stream                             */
+  int32_t q_len;           /* query tokens per sequence: 0 or 1 for every entry point but
+                              span_decode_attn_multi, which takes 1..64                          */
 } span_attn_desc_t;
 
 /*
@@ -103,6 +105,25 @@ typedef struct span_attn_desc {
 int span_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
                      const int32_t* span_offsets, const int32_t* span_starts, const int32_t* span_ends,
                      const int32_t* ctx_lens, float scale, float* out);
+
+/*
+ * Few-query variant: desc->q_len consecutive new tokens of every sequence attend in one call, all
+ * through the sequence's one span (a span is chosen once per group of tokens, Sec. 3.2, so the tokens
+ * of a group share it).  Among themselves the tokens keep the causal mask of Sec. 2.1: query token j
+ * of sequence b attends the span positions p <= q_pos[b] + j and no later one; eqs. (4)-(6) apply to
+ * each query row.  Every K / V row of the span is fetched once per pass and serves up to four query
+ * tokens; more than four take ceil(q_len / 4) passes.
+ *   q      : device, desc->dtype, [batch, q_len, heads, head_dim]
+ *   q_pos  : device int32 [batch], cache position of query token 0 (its K / V row, like those of the
+ *            other new tokens, is already in the cache and inside the span if it is to be attended);
+ *            NULL = no causal limit, every token attends the whole span
+ *   out    : device fp32 [batch, q_len, heads, head_dim]
+ * Everything else as for span_decode_attn; workspace size and plan depend on desc->q_len.  A query
+ * token that sees no span position gets an all-zero row.
+ */
+int span_decode_attn_multi(const span_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
+                           const int32_t* span_offsets, const int32_t* span_starts, const int32_t* span_ends,
+                           const int32_t* q_pos, float scale, float* out);
 
 /*
  * Dense control: the same computation over S_b = [0, ctx_lens[b]) with no span metadata (decode

@@ -26,7 +26,7 @@ class _Desc(ctypes.Structure):
                 ("max_len", ctypes.c_int32), ("dtype", ctypes.c_int32), ("num_intervals", ctypes.c_int32),
                 ("max_tokens", ctypes.c_int32), ("num_splits", ctypes.c_int32),
                 ("tokens_per_seq", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-                ("stream", ctypes.c_void_p)]
+                ("stream", ctypes.c_void_p), ("q_len", ctypes.c_int32)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -54,6 +54,8 @@ def load_library():
         DP = ctypes.POINTER(_Desc)
         lib.span_decode_attn.argtypes = [DP, P, P, P, P, P, P, P, F, P]
         lib.span_decode_attn.restype = ctypes.c_int
+        lib.span_decode_attn_multi.argtypes = [DP, P, P, P, P, P, P, P, F, P]
+        lib.span_decode_attn_multi.restype = ctypes.c_int
         lib.dense_decode_attn.argtypes = [DP, P, P, P, P, F, P]
         lib.dense_decode_attn.restype = ctypes.c_int
         lib.span_decode_attn_append.argtypes = [DP, P, P, P, P, P, P, P, P, P, F, P]
@@ -94,10 +96,10 @@ def _dtype_code(t):
 
 
 def make_desc(batch, heads, head_dim, max_len, dtype_code, num_intervals=0, max_tokens=0, num_splits=0,
-              workspace_ptr=0, workspace_bytes=0, stream=0, tokens_per_seq=None) -> _Desc:
+              workspace_ptr=0, workspace_bytes=0, stream=0, tokens_per_seq=None, q_len=0) -> _Desc:
     """tokens_per_seq: host int64 numpy array [batch] or None; the descriptor keeps a reference to it."""
     d = _Desc(batch, heads, head_dim, max_len, dtype_code, num_intervals, max_tokens, num_splits, None,
-              workspace_ptr or None, workspace_bytes, stream or None)
+              workspace_ptr or None, workspace_bytes, stream or None, int(q_len))
     if tokens_per_seq is not None:
         tok = np.ascontiguousarray(tokens_per_seq, dtype=np.int64).reshape(-1)
         if tok.shape[0] != batch:
@@ -225,13 +227,16 @@ def span_build(anchors, refs, prefix_end, prev_line_start, cur_line_start, ctx_l
         return list(zip(st[:n].tolist(), en[:n].tolist()))
 
 
-def _check_qkv(q, k_cache, v_cache):
+def _check_qkv(q, k_cache, v_cache, multi=False):
     if not (q.is_cuda and k_cache.is_cuda and v_cache.is_cuda):
         raise ValueError("q, k_cache and v_cache must be GPU tensors")
     if not (q.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous()):
         raise ValueError("q, k_cache and v_cache must be contiguous")
     B, H, L, D = k_cache.shape
-    if tuple(q.shape) != (B, H, D) or v_cache.shape != k_cache.shape:
+    if multi:
+        if q.dim() != 4 or (q.shape[0], q.shape[2], q.shape[3]) != (B, H, D) or v_cache.shape != k_cache.shape:
+            raise ValueError("expected q [B,Q,H,D] and k_cache / v_cache [B,H,L,D]")
+    elif tuple(q.shape) != (B, H, D) or v_cache.shape != k_cache.shape:
         raise ValueError("expected q [B,H,D] and k_cache / v_cache [B,H,L,D]")
     if not (q.dtype == k_cache.dtype == v_cache.dtype):
         raise ValueError("q, k_cache, v_cache must share one dtype")
@@ -245,17 +250,18 @@ def _i32_dev(t, n, name):
     return t.data_ptr()
 
 
-def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, workspace, stream, tokens_per_seq):
+def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, workspace, stream, tokens_per_seq,
+             multi=False):
     import torch
-    B, H, L, D = _check_qkv(q, k_cache, v_cache)
+    B, H, L, D = _check_qkv(q, k_cache, v_cache, multi)
     if out is None:
-        out = torch.empty((B, H, D), dtype=torch.float32, device=q.device)
-    elif out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous() or tuple(out.shape) != (B, H, D):
-        raise ValueError("out must be a contiguous fp32 GPU tensor [B,H,D]")
+        out = torch.empty(tuple(q.shape), dtype=torch.float32, device=q.device)
+    elif out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous() or out.shape != q.shape:
+        raise ValueError("out must be a contiguous fp32 GPU tensor shaped like q")
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
     desc = make_desc(B, H, D, L, _dtype_code(q), num_intervals, int(max_tokens), int(num_splits), 0, 0, stream,
-                     tokens_per_seq)
+                     tokens_per_seq, q_len=q.shape[1] if multi else 0)
     need = span_workspace_bytes(desc)
     if need:
         fresh = workspace is None
@@ -266,6 +272,30 @@ def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, wo
         if fresh:
             span_workspace_init(desc)   # a workspace handed in by the caller must already be initialised
     return desc, out, workspace
+
+
+def prepare_span_decode_attn_multi(q, k_cache, v_cache, span_offsets, span_starts, span_ends, q_pos, scale,
+                                   out=None, *, max_tokens=0, num_splits=0, workspace=None, stream=None,
+                                   tokens_per_seq=None) -> "PreparedCall":
+    """Few-query variant: q [B,Q,H,D], q_pos int32 GPU tensor [B] or None, out fp32 [B,Q,H,D]."""
+    lib = load_library()
+    n_int = int(span_starts.numel())
+    desc, out, workspace = _prepare(q, k_cache, v_cache, out, n_int, max_tokens, num_splits, workspace, stream,
+                                    tokens_per_seq, multi=True)
+    off_p = _i32_dev(span_offsets, desc.batch + 1, "span_offsets")
+    st_p = _i32_dev(span_starts, n_int, "span_starts")
+    en_p = _i32_dev(span_ends, n_int, "span_ends")
+    pos_p = _i32_dev(q_pos, desc.batch, "q_pos") if q_pos is not None else None
+    args = (ctypes.byref(desc), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), off_p, st_p, en_p, pos_p,
+            float(scale), out.data_ptr())
+    keep = (q, k_cache, v_cache, span_offsets, span_starts, span_ends, q_pos, workspace)
+    return PreparedCall("span_decode_attn_multi", lib.span_decode_attn_multi, desc, args, out, keep)
+
+
+def span_decode_attn_multi(q, k_cache, v_cache, span_offsets, span_starts, span_ends, q_pos, scale, out=None,
+                           **kw):
+    return prepare_span_decode_attn_multi(q, k_cache, v_cache, span_offsets, span_starts, span_ends, q_pos, scale,
+                                          out, **kw)()
 
 
 class PreparedCall:

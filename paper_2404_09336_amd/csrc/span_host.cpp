@@ -56,7 +56,21 @@ int check_desc(const span_attn_desc_t* d) {
   if ((int64_t)d->batch * d->heads > INT_MAX / 2) return SPAN_ERR_SHAPE;
   if (d->batch > 65535) return SPAN_ERR_SHAPE;  // grid z limit
   if (d->dtype != SPAN_F32 && d->dtype != SPAN_F16 && d->dtype != SPAN_BF16) return SPAN_ERR_DTYPE;
+  if (d->q_len < 0 || d->q_len > kMaxQueryTokens) return SPAN_ERR_SHAPE;
   return SPAN_OK;
+}
+
+int32_t query_tokens(const span_attn_desc_t* d) { return d->q_len > 1 ? d->q_len : 1; }
+
+// Query tokens one launch serves: 1, 2 or 4 (the kernel's register budget stops there).
+static int32_t queries_per_pass(const span_attn_desc_t* d) {
+  const int32_t n = query_tokens(d);
+  return n >= 3 ? 4 : n;
+}
+
+// Workgroups of one resident round: the one-query kernel runs 8 workgroups per CU, the few-query kernels 4.
+static int64_t target_workgroups(const span_attn_desc_t* d) {
+  return queries_per_pass(d) > 1 ? kTargetWorkgroups / 2 : kTargetWorkgroups;
 }
 
 static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -84,9 +98,10 @@ static bool plan_exact(const span_attn_desc_t* d, int64_t max_tok, Partition* p,
   };
   int64_t sum = 0;
   for (int32_t b = 0; b < d->batch; ++b) sum += tokens(b);
-  int64_t room = kTargetWorkgroups / d->heads;  // slices (per head) that fit in one round
+  const int64_t target = target_workgroups(d);
+  int64_t room = target / d->heads;  // slices (per head) that fit in one round
   if (room > kMaxPlanSlices) room = kMaxPlanSlices;
-  int64_t T = ceil_div(sum * d->heads, kTargetWorkgroups);
+  int64_t T = ceil_div(sum * d->heads, target);
   if (T < kMinSlice) T = kMinSlice;
   int64_t total = count(T);
   if (room < d->batch) {  // batch * heads alone exceeds a round: whole sequences
@@ -128,6 +143,7 @@ static bool plan_exact(const span_attn_desc_t* d, int64_t max_tok, Partition* p,
   p->slice_tokens = (int32_t)largest;
   p->max_tokens = (int32_t)max_tok;
   p->total_slices = (int32_t)total;
+  p->queries_per_pass = queries_per_pass(d);
   return true;
 }
 
@@ -139,7 +155,7 @@ Partition plan_partition(const span_attn_desc_t* d, uint32_t* table) {
   Partition p;
   if (plan_exact(d, max_tok, &p, table)) return p;
   const int64_t pairs = (int64_t)d->batch * d->heads;
-  int64_t splits = d->num_splits > 0 ? d->num_splits : kTargetWorkgroups / pairs;  // stay within one round
+  int64_t splits = d->num_splits > 0 ? d->num_splits : target_workgroups(d) / pairs;  // stay within one round
   const int64_t most = ceil_div(max_tok, kMinSlice);
   if (d->num_splits == 0 && splits > most) splits = most;
   if (splits > max_tok) splits = max_tok;
@@ -154,6 +170,7 @@ Partition plan_partition(const span_attn_desc_t* d, uint32_t* table) {
   p.slice_tokens = (int32_t)slice;
   p.max_tokens = (int32_t)max_tok;
   p.total_slices = (int32_t)(splits * d->batch);
+  p.queries_per_pass = queries_per_pass(d);
   return p;
 }
 
@@ -163,14 +180,14 @@ size_t workspace_counter_bytes(const span_attn_desc_t* d) {
 }
 
 size_t workspace_ml_bytes(const span_attn_desc_t* d, const Partition& p) {
-  const size_t n = (size_t)p.total_slices * d->heads * 2 * sizeof(float);
+  const size_t n = (size_t)p.total_slices * d->heads * p.queries_per_pass * 2 * sizeof(float);
   return (n + 255) & ~(size_t)255;
 }
 
 size_t workspace_bytes(const span_attn_desc_t* d, const Partition& p) {
   if (p.num_splits <= 1) return 0;
   return workspace_counter_bytes(d) + workspace_ml_bytes(d, p) +
-         (size_t)p.total_slices * d->heads * d->head_dim * sizeof(float);
+         (size_t)p.total_slices * d->heads * p.queries_per_pass * d->head_dim * sizeof(float);
 }
 
 }  // namespace spanattn

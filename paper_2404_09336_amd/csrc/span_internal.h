@@ -20,6 +20,7 @@ constexpr int kInterleaveFrom = 384;        // slices at least this large deal t
 constexpr int kMaxPlanSlices = 768;        // entries of the slice table passed as kernel argument
 constexpr int kMaxPlanBatch = 1024;        // 10 bits of a table entry
 constexpr int kMaxPlanSplits = 2047;       // 11 bits of a table entry
+constexpr int kMaxQueryTokens = 64;        // few-query variant: query tokens per sequence and call
 
 // Slice table entry (exact mode): batch index | slice index within the sequence | slices of the sequence.
 inline uint32_t pack_slice(uint32_t b, uint32_t split, uint32_t nsl) { return b | (split << 10) | (nsl << 21); }
@@ -31,6 +32,7 @@ struct Partition {
   int32_t slice_tokens;  // attended positions per slice (exact: upper bound)
   int32_t max_tokens;    // bound on attended positions per sequence
   int32_t total_slices;  // exact: table entries (grid.y); uniform: batch * num_splits
+  int32_t queries_per_pass;  // query tokens one launch serves (1, 2 or 4)
 };
 
 // Fills `table` (kMaxPlanSlices entries) when the partition is exact; table may be null to only size it.
@@ -38,6 +40,7 @@ Partition plan_partition(const span_attn_desc_t* d, uint32_t* table);
 inline Partition plan_partition(const span_attn_desc_t* d) { return plan_partition(d, nullptr); }
 
 int check_desc(const span_attn_desc_t* d);
+int32_t query_tokens(const span_attn_desc_t* d);  // q_len of the descriptor, at least 1
 size_t workspace_counter_bytes(const span_attn_desc_t* d);
 size_t workspace_ml_bytes(const span_attn_desc_t* d, const Partition& p);
 size_t workspace_bytes(const span_attn_desc_t* d, const Partition& p);

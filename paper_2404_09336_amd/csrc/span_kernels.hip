@@ -58,11 +58,14 @@ struct LaunchArgs {
   const void* k_new;           // append variant: the new token's K / V rows [batch, heads, D], else null
   const void* v_new;
   const int32_t* append_pos;   // append variant: [batch] cache row that receives them
+  const int32_t* q_pos;        // few-query variant: [batch] cache position of query token 0 (causal limit), or null
   int32_t* counters;  // [batch*heads] arrival tickets of the slices; zero between calls
   // one slot per workgroup, slot = (first slice row of the sequence + slice) * heads + head:
-  float* part_ml;   // [slots, 2]  (m in log2 units, l)
-  float* part_acc;  // [slots, D]  un-normalised
+  float* part_ml;   // [slots, NQ, 2]  (m in log2 units, l)
+  float* part_acc;  // [slots, NQ, D]  un-normalised
   int32_t heads, max_len, num_intervals, slice_tokens, num_splits, max_tokens;
+  int32_t q_len;                    // query tokens per sequence in q and out ([batch, q_len, heads, D])
+  int32_t q_first;                  // few-query variant: first query token this launch handles
   float scale_log2e;
   int32_t total_slices;             // table mode: entries of `table` in use
   int32_t even;                     // 1: a sequence's slices share its own token count evenly; 0: slice_tokens each
@@ -182,8 +185,11 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int 
 }
 
 // ---- the streaming kernel ------------------------------------------------------------------------
-template <class Elt, int D, bool kDense, int U, class Args>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void decode_kernel(const Args a) {
+// NQ query tokens per sequence are served by one pass over the span's rows (NQ = 1: the decode step proper).
+// The register budget is 64 per lane for one query (8 waves per SIMD) and 128 for several (4 per SIMD).
+template <class Elt, int D, bool kDense, int U, int NQ, class Args>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 1 ? 8 : 4, NQ == 1 ? 8 : 4))) void decode_kernel(
+    const Args a) {
   constexpr int EPL = Elt::kPerVec;        // elements per lane (one 128-bit piece)
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPL = 64 / LPR;            // rows per wave-wide load
@@ -226,19 +232,28 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   __shared__ u32x4 s_new[kWavesPerBlock][2][LPR];  // append variant: the new K / V row, parked until its owner needs it
   __shared__ int s_pref[kWavesPerBlock][64];
   __shared__ int s_start[kWavesPerBlock][64];
-  __shared__ float s_acc[kWavesPerBlock][D];
-  __shared__ float s_ml[kWavesPerBlock][2];
-  __shared__ float s_gm[kWavesPerBlock][D], s_gl[kWavesPerBlock][D];
+  __shared__ float s_acc[kWavesPerBlock][NQ][D];
+  __shared__ float s_ml[kWavesPerBlock][NQ][2];
+  __shared__ float s_gm[kWavesPerBlock][NQ], s_gl[kWavesPerBlock][NQ];
   __shared__ int s_ticket;
 
-  // q piece of this lane, pre-multiplied by scale*log2(e) so that exp() becomes exp2().
-  float qf[EPL];
-  {
-    const u32x4 qr = *reinterpret_cast<const u32x4*>((const char*)a.q + bh * ROWB + (uint32_t)lir * 16u);
-    Elt::unpack(qr, qf);
+  // Query token j of this launch is row (b, q_first + j, h) of q and out; a launch whose last tokens do
+  // not exist (q_len not a multiple of NQ) computes them from the last real one and never writes them.
+  const int nq_here = min(NQ, a.q_len - a.q_first);
+  auto qrow = [&](int j) { return ((size_t)b * a.q_len + (size_t)(a.q_first + min(j, nq_here - 1))) * a.heads + h; };
+  // q pieces of this lane, pre-multiplied by scale*log2(e) so that exp() becomes exp2().
+  float qf[NQ][EPL];
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) qf[i] *= a.scale_log2e;
+  for (int j = 0; j < NQ; ++j) {
+    const u32x4 qr = *reinterpret_cast<const u32x4*>((const char*)a.q + qrow(j) * ROWB + (uint32_t)lir * 16u);
+    Elt::unpack(qr, qf[j]);
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) qf[j][i] *= a.scale_log2e;
   }
+  // Causal limit (few-query variant): query token j sees no position after its own, q_pos[b] + q_first + j.
+  int lim[NQ];
+#pragma unroll
+  for (int j = 0; j < NQ; ++j) lim[j] = a.q_pos ? a.q_pos[b] + a.q_first + j : 0x7fffffff;
 
   // ---- step 1: how many attended positions does the sequence have, which are mine ----------------
   // with fixed-size slices the count may stop at the slice's end; even slices need the sequence's total
@@ -270,8 +285,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   const int slice_begin = split * T;
   const int cnt = __builtin_amdgcn_readfirstlane(clampi(n_total - slice_begin, 0, T));
 
-  // State of this slice for output column tid (tid < D): un-normalised, m in log2 units.
-  float M = -INFINITY, L = 0.f, o = 0.f;
+  // State of this slice for output column tid (tid < D), per query token: un-normalised, m in log2 units.
+  float M[NQ], L[NQ], o[NQ];
+#pragma unroll
+  for (int j = 0; j < NQ; ++j) {
+    M[j] = -INFINITY;
+    L[j] = 0.f;
+    o[j] = 0.f;
+  }
   if (cnt > 0) {  // same decision in all 4 waves
   // How the slice's rows are dealt to the 4 waves.  My rows are numbered r = 0..nrows-1; row r is
   // virtual token vrow(r) of the sequence.
@@ -303,10 +324,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   const __amdgpu_buffer_rsrc_t vslab = slab_resource((const char*)a.v + bh * (size_t)slab_bytes, slab_bytes);
   const uint32_t lane_off = (uint32_t)lir * 16u;
 
-  float m = -INFINITY, l = 0.f;
-  float acc[EPL];
+  float m[NQ], l[NQ];
+  float acc[NQ][EPL];
 #pragma unroll
-  for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+  for (int j = 0; j < NQ; ++j) {
+    m[j] = -INFINITY;
+    l[j] = 0.f;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[j][i] = 0.f;
+  }
 
   if (a.append_pos) {
     if (lane < LPR) {  // park the new row in LDS (frees the registers); the first slice also writes the cache
@@ -386,11 +412,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
       Elt::unpack(s_new[wave][1][lir], vf);
       float d = 0.f;
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[i], d);
+      for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[0][i], d);
       d = group_allreduce_sum<LPR>(d);
       if (grp == 0) {
         const float l_one = 1.f;
-        merge_state(m, l, acc, EPL, d, l_one, vf);
+        merge_state(m[0], l[0], acc[0], EPL, d, l_one, vf);
       }
     }
   }
@@ -399,85 +425,111 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   for (int base = 0; base < wn; base += RPL * U) {
     u32x4 kr[U], vr[U];
     bool ok[U];
+    int pos[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = base + u * RPL + grp;
       ok[u] = r < wn;
       const int rc = ok[u] ? r : wn - 1;  // a row past the end re-reads the last one with weight 0
       const int p = kDense ? vrow(w0 + rc) : s_pos[wave][rc];
+      pos[u] = p;
       // the appended row is not in the cache yet for this launch: request an offset past the slab
       // (the buffer hardware returns zeros) and give it no weight here; its owner added it above
       const bool is_new = p == new_pos;
       ok[u] = ok[u] && !is_new;
+      if (NQ == 1) ok[u] = ok[u] && p <= lim[0];  // one query: its limit is settled here, not per score
       const uint32_t off = is_new ? 0xfffffff0u : (uint32_t)p * ROWB + lane_off;
       kr[u] = load_row_piece(kslab, off);
       vr[u] = load_row_piece(vslab, off);
     }
-    float s[U];
-    float mx = -INFINITY;
+    float w[NQ][U];  // scores first, then softmax weights
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       float kf[EPL];
       Elt::unpack(kr[u], kf);
-      float d = 0.f;
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[i], d);
-      d = group_allreduce_sum<LPR>(d);
-      s[u] = ok[u] ? d : -INFINITY;
-      mx = fmaxf(mx, s[u]);
+      for (int j = 0; j < NQ; ++j) {
+        float d = 0.f;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[j][i], d);
+        d = group_allreduce_sum<LPR>(d);
+        w[j][u] = (ok[u] && (NQ == 1 || pos[u] <= lim[j])) ? d : -INFINITY;
+      }
     }
-    const float m_new = fmaxf(m, mx);
-    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m - m_safe);
-    l *= alpha;
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) acc[i] *= alpha;
+    for (int j = 0; j < NQ; ++j) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < U; ++u) mx = fmaxf(mx, w[j][u]);
+      const float m_new = fmaxf(m[j], mx);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m[j] - m_safe);
+      l[j] *= alpha;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) acc[j][i] *= alpha;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        w[j][u] = __builtin_amdgcn_exp2f(w[j][u] - m_safe);
+        l[j] += w[j][u];
+      }
+      m[j] = m_new;
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float p = __builtin_amdgcn_exp2f(s[u] - m_safe);
-      l += p;
       float vf[EPL];
       Elt::unpack(vr[u], vf);
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) acc[i] = fmaf(p, vf[i], acc[i]);
+      for (int j = 0; j < NQ; ++j) {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[j][i] = fmaf(w[j][u], vf[i], acc[j][i]);
+      }
     }
-    m = m_new;
   }
   }  // windows
 
   // ---- step 4: merge row groups (shuffles), then waves (LDS) ------------------------------------
 #pragma unroll
-  for (int off = LPR; off < 64; off <<= 1) {
-    const float m2 = __shfl_xor(m, off, 64), l2 = __shfl_xor(l, off, 64);
-    float acc2[EPL];
+  for (int j = 0; j < NQ; ++j) {
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) acc2[i] = __shfl_xor(acc[i], off, 64);
-    merge_state(m, l, acc, EPL, m2, l2, acc2);
-  }
-  if (lane < LPR) {
+    for (int off = LPR; off < 64; off <<= 1) {
+      const float m2 = __shfl_xor(m[j], off, 64), l2 = __shfl_xor(l[j], off, 64);
+      float acc2[EPL];
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) s_acc[wave][lir * EPL + i] = acc[i];
-    if (lane == 0) {
-      s_ml[wave][0] = m;
-      s_ml[wave][1] = l;
+      for (int i = 0; i < EPL; ++i) acc2[i] = __shfl_xor(acc[j][i], off, 64);
+      merge_state(m[j], l[j], acc[j], EPL, m2, l2, acc2);
+    }
+    if (lane < LPR) {
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) s_acc[wave][j][lir * EPL + i] = acc[j][i];
+      if (lane == 0) {
+        s_ml[wave][j][0] = m[j];
+        s_ml[wave][j][1] = l[j];
+      }
     }
   }
   __syncthreads();
   if (tid < D) {
 #pragma unroll
-    for (int w = 0; w < kWavesPerBlock; ++w)
-      if (s_ml[w][1] > 0.f) M = fmaxf(M, s_ml[w][0]);
+    for (int j = 0; j < NQ; ++j) {
 #pragma unroll
-    for (int w = 0; w < kWavesPerBlock; ++w) {
-      const float wgt = s_ml[w][1] > 0.f ? __builtin_amdgcn_exp2f(s_ml[w][0] - M) : 0.f;
-      L += wgt * s_ml[w][1];
-      o += wgt * s_acc[w][tid];
+      for (int w = 0; w < kWavesPerBlock; ++w)
+        if (s_ml[w][j][1] > 0.f) M[j] = fmaxf(M[j], s_ml[w][j][0]);
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w) {
+        const float wgt = s_ml[w][j][1] > 0.f ? __builtin_amdgcn_exp2f(s_ml[w][j][0] - M[j]) : 0.f;
+        L[j] += wgt * s_ml[w][j][1];
+        o[j] += wgt * s_acc[w][j][tid];
+      }
     }
   }
   }  // cnt > 0
 
   if (nsl == 1) {  // one slice for this (batch, head): this workgroup owns the output row
-    if (tid < D) a.out[bh * D + tid] = L > 0.f ? o / L : 0.f;
+    if (tid < D) {
+#pragma unroll
+      for (int j = 0; j < NQ; ++j)
+        if (j < nq_here) a.out[qrow(j) * D + tid] = L[j] > 0.f ? o[j] / L[j] : 0.f;
+    }
     return;
   }
 
@@ -493,10 +545,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
   const size_t H = (size_t)a.heads;
   const size_t my_slot = (size_t)(y0 + split) * H + h;
   if (tid < D) {
-    if (cnt > 0) publish(&a.part_acc[my_slot * D + tid], o);
-    if (tid == 0) {
-      publish(&a.part_ml[my_slot * 2], M);
-      publish(&a.part_ml[my_slot * 2 + 1], L);
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+      if (cnt > 0) publish(&a.part_acc[(my_slot * NQ + j) * D + tid], o[j]);
+      if (tid == 0) {
+        publish(&a.part_ml[(my_slot * NQ + j) * 2], M[j]);
+        publish(&a.part_ml[(my_slot * NQ + j) * 2 + 1], L[j]);
+      }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my published stores are acknowledged
   }
@@ -507,29 +562,46 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
 
   constexpr int G = kThreads / D;  // column t is merged by G threads, each over every G-th slice
   const int g = tid / D, t = tid % D;
-  const float* ml = a.part_ml + ((size_t)y0 * H + h) * 2;
-  const float* pa = a.part_acc + ((size_t)y0 * H + h) * D;
-  float mm = -INFINITY, ll = 0.f, oo = 0.f;
+  const size_t slot0 = (size_t)y0 * H + h;  // slice s of this (b, h) is slot0 + s * H
+  float mm[NQ], ll[NQ], oo[NQ];
+#pragma unroll
+  for (int j = 0; j < NQ; ++j) {
+    mm[j] = -INFINITY;
+    ll[j] = 0.f;
+    oo[j] = 0.f;
+  }
 #pragma unroll 4
   for (int s = g; s < nsl; s += G) {
-    const float ms = observe(&ml[(size_t)s * H * 2]), ls = observe(&ml[(size_t)s * H * 2 + 1]);
-    float as = observe(&pa[(size_t)s * H * D + t]);  // slot of an empty slice is never written: select, do not scale
-    as = ls > 0.f ? as : 0.f;
-    merge_state(mm, ll, &oo, 1, ls > 0.f ? ms : -INFINITY, ls > 0.f ? ls : 0.f, &as);
+    const size_t slot = slot0 + (size_t)s * H;
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+      const float ms = observe(&a.part_ml[(slot * NQ + j) * 2]), ls = observe(&a.part_ml[(slot * NQ + j) * 2 + 1]);
+      float as = observe(&a.part_acc[(slot * NQ + j) * D + t]);  // slot of an empty slice is never written: select, do not scale
+      as = ls > 0.f ? as : 0.f;
+      merge_state(mm[j], ll[j], &oo[j], 1, ls > 0.f ? ms : -INFINITY, ls > 0.f ? ls : 0.f, &as);
+    }
   }
   if (g > 0) {
-    s_acc[g][t] = oo;
-    s_gm[g][t] = mm;
-    s_gl[g][t] = ll;
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+      s_acc[g][j][t] = oo[j];
+      if (t == 0) {
+        s_gm[g][j] = mm[j];
+        s_gl[g][j] = ll[j];
+      }
+    }
   }
   __syncthreads();
   if (g == 0) {
 #pragma unroll
-    for (int j = 1; j < G; ++j) {
-      const float o2 = s_acc[j][t];
-      merge_state(mm, ll, &oo, 1, s_gm[j][t], s_gl[j][t], &o2);
+    for (int j = 0; j < NQ; ++j) {
+#pragma unroll
+      for (int k = 1; k < G; ++k) {
+        const float o2 = s_acc[k][j][t];
+        merge_state(mm[j], ll[j], &oo[j], 1, s_gm[k][j], s_gl[k][j], &o2);
+      }
+      if (j < nq_here) a.out[qrow(j) * D + t] = ll[j] > 0.f ? oo[j] / ll[j] : 0.f;
     }
-    a.out[bh * D + t] = ll > 0.f ? oo / ll : 0.f;
     // leave the ticket counter ready for the next call (same device-coherent access path as the tickets)
     if (tid == 0) __hip_atomic_store(&a.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
@@ -543,20 +615,21 @@ __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, size_t n) 
 
 thread_local int g_last_hip_error = 0;
 
-template <class Elt, int D, bool kDense>
+template <class Elt, int D, bool kDense, int NQ>
 int launch_typed(const LaunchArgsTable& a, bool use_table, int batch, hipStream_t stream) {
   // K loads (and as many V loads) a wave has in flight before it consumes the first: 4 KiB + 4 KiB, but
-  // never more than 16 rows (with 128-byte rows that is 2 instructions of 8 rows)
+  // never more than 16 rows (with 128-byte rows that is 2 instructions of 8 rows); half of that when
+  // several query tokens share the registers
   constexpr int kRowsPerLoad = 64 / (D / Elt::kPerVec);
-  constexpr int kInFlight = kRowsPerLoad >= 8 ? 2 : 4;
+  constexpr int kInFlight = (kRowsPerLoad >= 8 ? 2 : 4) / (NQ > 1 ? 2 : 1);
   if (use_table) {
     const dim3 grid((unsigned)a.heads, (unsigned)a.total_slices, 1u);
-    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, LaunchArgsTable>), grid, dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsTable>), grid, dim3(kThreads), 0, stream, a);
   } else {
     const dim3 grid((unsigned)a.heads, (unsigned)a.num_splits, (unsigned)batch);
     LaunchArgsPlain plain;
     static_cast<LaunchArgs&>(plain) = static_cast<const LaunchArgs&>(a);
-    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, LaunchArgsPlain>), grid, dim3(kThreads), 0, stream, plain);
+    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsPlain>), grid, dim3(kThreads), 0, stream, plain);
   }
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) {
@@ -566,12 +639,23 @@ int launch_typed(const LaunchArgsTable& a, bool use_table, int batch, hipStream_
   return SPAN_OK;
 }
 
+template <class Elt, int D, bool kDense>
+int launch_queries(const LaunchArgsTable& a, int nq, bool use_table, int batch, hipStream_t stream) {
+  if constexpr (!kDense) {  // the few-query variant exists for the span form only
+    if (nq == 2) return launch_typed<Elt, D, false, 2>(a, use_table, batch, stream);
+    if (nq == 4) return launch_typed<Elt, D, false, 4>(a, use_table, batch, stream);
+  }
+  return launch_typed<Elt, D, kDense, 1>(a, use_table, batch, stream);
+}
+
 template <bool kDense>
 int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* v, const int32_t* offsets,
            const int32_t* starts, const int32_t* ends, const int32_t* ctx_lens, float scale, float* out,
-           const void* k_new = nullptr, const void* v_new = nullptr, const int32_t* append_pos = nullptr) {
+           const void* k_new = nullptr, const void* v_new = nullptr, const int32_t* append_pos = nullptr,
+           const int32_t* q_pos = nullptr, bool few_query = false) {
   const int rc = check_desc(d);
   if (rc != SPAN_OK) return rc;
+  if (query_tokens(d) > 1 && !few_query) return SPAN_ERR_SHAPE;  // only span_decode_attn_multi takes several
   if (!q || !k || !v || !out) return SPAN_ERR_NULL;
   if (kDense ? !ctx_lens : (!offsets || (d->num_intervals > 0 && (!starts || !ends)))) return SPAN_ERR_NULL;
   LaunchArgsTable a;
@@ -591,6 +675,8 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   a.k_new = k_new;
   a.v_new = v_new;
   a.append_pos = append_pos;
+  a.q_pos = q_pos;
+  a.q_len = query_tokens(d);
   a.counters = need ? (int32_t*)d->workspace : nullptr;
   a.part_ml = need ? (float*)((char*)d->workspace + workspace_counter_bytes(d)) : nullptr;
   a.part_acc = need ? (float*)((char*)d->workspace + workspace_counter_bytes(d) + workspace_ml_bytes(d, p)) : nullptr;
@@ -606,15 +692,30 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   a.scale_log2e = scale * 1.4426950408889634f;
   hipStream_t stream = (hipStream_t)d->stream;
 
+  // One pass over the span serves up to p.queries_per_pass query tokens; more tokens take more passes,
+  // one after the other on the stream (they share the workspace).
   const bool d128 = d->head_dim == 128;
-  switch (d->dtype) {
-    case SPAN_F32:
-      return d128 ? launch_typed<F32, 128, kDense>(a, p.exact, d->batch, stream) : launch_typed<F32, 64, kDense>(a, p.exact, d->batch, stream);
-    case SPAN_F16:
-      return d128 ? launch_typed<F16, 128, kDense>(a, p.exact, d->batch, stream) : launch_typed<F16, 64, kDense>(a, p.exact, d->batch, stream);
-    default:
-      return d128 ? launch_typed<BF16, 128, kDense>(a, p.exact, d->batch, stream) : launch_typed<BF16, 64, kDense>(a, p.exact, d->batch, stream);
+  for (int32_t first = 0; first < a.q_len; first += p.queries_per_pass) {
+    a.q_first = first;
+    const int nq = p.queries_per_pass;
+    int lrc;
+    switch (d->dtype) {
+      case SPAN_F32:
+        lrc = d128 ? launch_queries<F32, 128, kDense>(a, nq, p.exact, d->batch, stream)
+                   : launch_queries<F32, 64, kDense>(a, nq, p.exact, d->batch, stream);
+        break;
+      case SPAN_F16:
+        lrc = d128 ? launch_queries<F16, 128, kDense>(a, nq, p.exact, d->batch, stream)
+                   : launch_queries<F16, 64, kDense>(a, nq, p.exact, d->batch, stream);
+        break;
+      default:
+        lrc = d128 ? launch_queries<BF16, 128, kDense>(a, nq, p.exact, d->batch, stream)
+                   : launch_queries<BF16, 64, kDense>(a, nq, p.exact, d->batch, stream);
+        break;
+    }
+    if (lrc != SPAN_OK) return lrc;
   }
+  return SPAN_OK;
 }
 
 }  // namespace
@@ -625,6 +726,13 @@ extern "C" int span_decode_attn(const span_attn_desc_t* desc, const void* q, con
                                 const int32_t* span_ends, const int32_t* ctx_lens, float scale, float* out) {
   (void)ctx_lens;
   return spanattn::launch<false>(desc, q, k_cache, v_cache, span_offsets, span_starts, span_ends, nullptr, scale, out);
+}
+
+extern "C" int span_decode_attn_multi(const span_attn_desc_t* desc, const void* q, const void* k_cache,
+                                      const void* v_cache, const int32_t* span_offsets, const int32_t* span_starts,
+                                      const int32_t* span_ends, const int32_t* q_pos, float scale, float* out) {
+  return spanattn::launch<false>(desc, q, k_cache, v_cache, span_offsets, span_starts, span_ends, nullptr, scale, out,
+                                 nullptr, nullptr, nullptr, q_pos, true);
 }
 
 extern "C" int dense_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_cache,

@@ -1,0 +1,149 @@
+"""Parity of the few-query entry point (several new tokens of a sequence share its span, each under the
+causal limit) against the fp64 oracle, through the C ABI.  Same tolerances as the single-query path."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2404_09336_amd as span
+from workloads import CONFIGS, DecodeConfig, SpanBatch, draw_qkv, draw_queries, draw_spans, to_host_raw
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}
+
+
+def _dev(a, device):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def run_multi(cfg, sp, q, K, V, q_pos, device, **kw):
+    code, _, _, tok = span.span_validate(sp.offsets, sp.starts, sp.ends, sp.ctx_lens)
+    assert code == 0
+    kw.setdefault("max_tokens", int(tok.max()))
+    kw.setdefault("tokens_per_seq", tok)
+    out = span.span_decode_attn_multi(q, K, V, _dev(sp.offsets, device), _dev(sp.starts, device),
+                                      _dev(sp.ends, device), None if q_pos is None else _dev(q_pos, device),
+                                      np.float32(cfg.scale), **kw)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+def oracle_multi(cfg, sp, q, K, V, q_pos):
+    return oracle.span_attn_multi(to_host_raw(q), to_host_raw(K), to_host_raw(V), sp.offsets, sp.starts, sp.ends,
+                                  q_pos, np.float32(cfg.scale), dtype=cfg.dtype)
+
+
+def check(got, ref, tol, what):
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = float(np.abs(got - ref).max())
+    print(f"[parity] {what}: max-abs err {err:.3e} (tol {tol:g})", flush=True)
+    assert err <= tol, f"{what}: max-abs err {err:.3e} > {tol:g}"
+
+
+def new_tokens_at_the_end(sp, q_len):
+    """The q_len new tokens are the last q_len cache rows of each sequence; token 0 sits at ctx_len - q_len."""
+    return (sp.ctx_lens.astype(np.int64) - q_len).astype(np.int32)
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("q_len", [2, 4])
+def test_workload_multi_parity(cid, q_len, gpu_device):
+    """The five workloads: every span ends with the recent-token interval, so the new tokens are inside it."""
+    cfg = CONFIGS[cid]
+    sp = draw_spans(cfg)
+    _, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device)
+    q = draw_queries(cfg, q_len, device=gpu_device)
+    q_pos = new_tokens_at_the_end(sp, q_len)
+    ref = oracle_multi(cfg, sp, q, K, V, q_pos)
+    check(run_multi(cfg, sp, q, K, V, q_pos, gpu_device), ref, cfg.tol, f"config {cid}, {q_len} query tokens")
+    check(run_multi(cfg, sp, q, K, V, q_pos, gpu_device, tokens_per_seq=None), ref, cfg.tol,
+          f"config {cid}, {q_len} query tokens, uniform grid")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("q_len", [1, 2, 3, 4, 5, 8])
+def test_multi_all_kernel_instances(dtype, D, q_len, gpu_device):
+    """Every (type, head_dim) instance, token counts that pad a pass (3), fill it (2, 4) and need several (5, 8);
+    ragged sequences, forced slicing so that the cross-workgroup merge runs per query token."""
+    cfg = DecodeConfig(91, "multi", 3, 5, D, 700, 300, dtype, TOL[dtype])
+    rng = np.random.default_rng(100 * D + q_len)
+    ctx = rng.integers(cfg.min_len, cfg.max_len + 1, size=cfg.batch).astype(np.int32)
+    per_seq = []
+    for b in range(cfg.batch):
+        n = int(ctx[b])
+        a = int(rng.integers(1, 40))
+        s1 = int(rng.integers(a + 1, n // 2))
+        e1 = int(rng.integers(s1 + 1, n // 2 + 60))
+        per_seq.append([(0, a), (s1, e1), (n - 37, n)])
+    sp = SpanBatch.from_lists(per_seq, ctx)
+    _, K, V = draw_qkv(cfg, ctx, seed=cfg.seed() + q_len, device=gpu_device)
+    q = draw_queries(cfg, q_len, device=gpu_device)
+    q_pos = new_tokens_at_the_end(sp, q_len)
+    ref = oracle_multi(cfg, sp, q, K, V, q_pos)
+    check(run_multi(cfg, sp, q, K, V, q_pos, gpu_device), ref, cfg.tol, f"{dtype} D={D} q_len={q_len}")
+    for splits in (3, 7):
+        check(run_multi(cfg, sp, q, K, V, q_pos, gpu_device, num_splits=splits, tokens_per_seq=None), ref, cfg.tol,
+              f"{dtype} D={D} q_len={q_len} splits={splits}")
+    ref_all = oracle_multi(cfg, sp, q, K, V, None)
+    check(run_multi(cfg, sp, q, K, V, None, gpu_device), ref_all, cfg.tol, f"{dtype} D={D} q_len={q_len} no limit")
+
+
+def test_multi_limit_cases(gpu_device):
+    """Limits that fall before the span (zero rows), inside an interval, in a gap, and beyond the cache."""
+    cfg = DecodeConfig(92, "multi-limits", 5, 4, 128, 600, 600, "f16", 2e-3)
+    ctx = np.full(cfg.batch, 600, np.int32)
+    per_seq = [[(10, 50), (300, 420)]] * cfg.batch
+    sp = SpanBatch.from_lists(per_seq, ctx)
+    _, K, V = draw_qkv(cfg, ctx, device=gpu_device)
+    q = draw_queries(cfg, 4, device=gpu_device)
+    q_pos = np.array([5, 8, 48, 100, 598], np.int32)   # nothing / first rows appear / interval end / gap / all
+    ref = oracle_multi(cfg, sp, q, K, V, q_pos)
+    got = run_multi(cfg, sp, q, K, V, q_pos, gpu_device)
+    check(got, ref, cfg.tol, "limit cases")
+    assert np.array_equal(got[0], np.zeros_like(got[0]))            # tokens at 5..8 see nothing of [10, 50)
+    assert np.array_equal(got[1, :2], np.zeros_like(got[1, :2]))    # tokens at 8, 9 see nothing; 10, 11 do
+    assert np.abs(got[1, 2:]).max() > 0
+    for splits in (2, 5):
+        check(run_multi(cfg, sp, q, K, V, q_pos, gpu_device, num_splits=splits, tokens_per_seq=None), ref, cfg.tol,
+              f"limit cases, {splits} slices")
+
+
+def test_one_token_through_the_multi_entry_equals_the_decode_call(gpu_device):
+    cfg = CONFIGS[2]
+    sp = draw_spans(cfg)
+    q1, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device)
+    dev = lambda a: _dev(a, gpu_device)
+    tok = sp.tokens_per_seq()
+    single = span.span_decode_attn(q1, K, V, dev(sp.offsets), dev(sp.starts), dev(sp.ends), dev(sp.ctx_lens),
+                                   np.float32(cfg.scale), max_tokens=int(tok.max()), tokens_per_seq=tok)
+    multi = span.span_decode_attn_multi(q1[:, None].contiguous(), K, V, dev(sp.offsets), dev(sp.starts),
+                                        dev(sp.ends), None, np.float32(cfg.scale), max_tokens=int(tok.max()),
+                                        tokens_per_seq=tok)
+    torch.cuda.synchronize()
+    assert torch.equal(single, multi[:, 0])
+    # with a limit: one token that may not see the last 10 rows of its span
+    q_pos = (sp.ctx_lens - 11).astype(np.int32)
+    got = run_multi(cfg, sp, q1[:, None].contiguous(), K, V, q_pos, gpu_device)
+    check(got, oracle_multi(cfg, sp, q1[:, None].contiguous(), K, V, q_pos), cfg.tol, "one token with a limit")
+
+
+def test_single_query_entry_points_reject_several_tokens(gpu_device):
+    cfg = CONFIGS[1]
+    sp = draw_spans(cfg)
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device)
+    lib = span.load_library()
+    from paper_2404_09336_amd.binding import make_desc
+    import ctypes
+    d = make_desc(cfg.batch, cfg.heads, cfg.head_dim, cfg.max_len, 0, int(sp.starts.size), q_len=2)
+    out = torch.zeros((cfg.batch, cfg.heads, cfg.head_dim), device=gpu_device)
+    dev = lambda a: _dev(a, gpu_device)
+    off, st, en = dev(sp.offsets), dev(sp.starts), dev(sp.ends)
+    rc = lib.span_decode_attn(ctypes.byref(d), q.data_ptr(), K.data_ptr(), V.data_ptr(), off.data_ptr(),
+                              st.data_ptr(), en.data_ptr(), None, 0.1, out.data_ptr())
+    assert rc == -2   # SPAN_ERR_SHAPE
+    d.q_len = 65
+    rc = lib.span_decode_attn_multi(ctypes.byref(d), q.data_ptr(), K.data_ptr(), V.data_ptr(), off.data_ptr(),
+                                    st.data_ptr(), en.data_ptr(), None, 0.1, out.data_ptr())
+    assert rc == -2

@@ -7,10 +7,10 @@ the CPU oracle can be fed from it without sharing any code of their own.
 """
 from .configs import CONFIGS, DecodeConfig, get_config
 from .spans import SpanBatch, draw_spans, place_disjoint, full_cover_spans, microbench_spans
-from .tensors import draw_qkv, to_host_raw, torch_dtype
+from .tensors import draw_qkv, draw_queries, to_host_raw, torch_dtype
 
 __all__ = [
     "CONFIGS", "DecodeConfig", "get_config",
     "SpanBatch", "draw_spans", "place_disjoint", "full_cover_spans", "microbench_spans",
-    "draw_qkv", "to_host_raw", "torch_dtype",
+    "draw_qkv", "draw_queries", "to_host_raw", "torch_dtype",
 ]

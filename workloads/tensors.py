@@ -38,6 +38,15 @@ def draw_qkv(cfg: DecodeConfig, ctx_lens, seed=None, device="cpu", poison=True):
     return q, K, V
 
 
+def draw_queries(cfg: DecodeConfig, q_len: int, seed=None, device="cpu"):
+    """Query rows of `q_len` consecutive new tokens per sequence: [batch, q_len, heads, head_dim]."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(int(cfg.seed() if seed is None else seed) + 7919 * int(q_len))
+    q = torch.randn((cfg.batch, int(q_len), cfg.heads, cfg.head_dim), generator=gen, device=dev, dtype=torch.float32)
+    return q.to(torch_dtype(cfg.dtype))
+
+
 def to_host_raw(t: torch.Tensor) -> np.ndarray:
     """Host copy with the exact bits: float32 stays float32; fp16 / bf16 become uint16 bit patterns."""
     t = t.detach().contiguous().cpu()

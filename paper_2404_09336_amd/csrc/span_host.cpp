@@ -68,9 +68,11 @@ static int32_t queries_per_pass(const span_attn_desc_t* d) {
   return n >= 3 ? 4 : n;
 }
 
-// Workgroups of one resident round: the one-query kernel runs 8 workgroups per CU, the few-query kernels 4.
+// Workgroups of one resident round: the kernel for one query token runs 8 workgroups per CU, the one for
+// two tokens 6 and the one for four tokens 4 (their register budgets).
 static int64_t target_workgroups(const span_attn_desc_t* d) {
-  return queries_per_pass(d) > 1 ? kTargetWorkgroups / 2 : kTargetWorkgroups;
+  const int32_t nq = queries_per_pass(d);
+  return nq == 1 ? kTargetWorkgroups : (nq == 2 ? kTargetWorkgroups * 3 / 4 : kTargetWorkgroups / 2);
 }
 
 static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -117,6 +119,26 @@ static bool plan_exact(const span_attn_desc_t* d, int64_t max_tok, Partition* p,
     for (int i = 0; i < 8 && T - kSliceGranule >= kMinSlice && count(T - kSliceGranule) <= room; ++i)
       T -= kSliceGranule;
     total = count(T);
+  }
+  // One round cannot always be level: when batch * heads (nearly) fills it, long and short sequences are
+  // each one slice.  If the largest slice is then well above the average and large in itself, several
+  // rounds of kLargeSlice-sized slices do better: their start-up hides behind the neighbours' streaming and
+  // the hardware deals them to whichever CU is free.  (Level plans are left alone: cutting them further
+  // only adds partial states; measured 2-4 % slower.)  The slice table bounds the number of slices.
+  {
+    int64_t largest_now = 1;
+    for (int32_t b = 0; b < d->batch; ++b) {
+      const int64_t n = tokens(b), per = ceil_div(n, slices_for(n, T));
+      if (per > largest_now) largest_now = per;
+    }
+    if (largest_now > kLargeSlice && 2 * largest_now * total > 3 * sum) {
+      int64_t T2 = kLargeSlice;
+      while (T2 < T && count(T2) > kMaxPlanSlices) T2 += kLargeSlice / 4;
+      if (T2 < T) {
+        T = T2;
+        total = count(T);
+      }
+    }
   }
   int64_t most = 1, least = kMaxPlanSplits + 1, largest = 1;
   for (int32_t b = 0; b < d->batch; ++b) {

@@ -186,9 +186,9 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int 
 
 // ---- the streaming kernel ------------------------------------------------------------------------
 // NQ query tokens per sequence are served by one pass over the span's rows (NQ = 1: the decode step proper).
-// The register budget is 64 per lane for one query (8 waves per SIMD) and 128 for several (4 per SIMD).
+// The register budget is 64 per lane for one query (8 waves per SIMD), 80 for two (6) and 128 for four (4).
 template <class Elt, int D, bool kDense, int U, int NQ, class Args>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 1 ? 8 : 4, NQ == 1 ? 8 : 4))) void decode_kernel(
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 1 ? 8 : (NQ == 2 ? 6 : 4), NQ == 1 ? 8 : (NQ == 2 ? 6 : 4)))) void decode_kernel(
     const Args a) {
   constexpr int EPL = Elt::kPerVec;        // elements per lane (one 128-bit piece)
   constexpr int LPR = D / EPL;             // lanes per row

@@ -42,6 +42,7 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = kWavesPerBlock * 64;
 constexpr int kWin = 256;  // rows of a wave whose positions are tabulated at a time (one LDS window)
@@ -82,9 +83,18 @@ struct LaunchArgsPlain : LaunchArgs {
   static constexpr bool kHasTable = false;
 };
 
-// ---- storage types: 16 bytes of a row -> fp32 --------------------------------------------------
+// ---- storage types ---------------------------------------------------------------------------------
+// unpack: 16 bytes of a row -> fp32 (for the V accumulation).
+// The q.k partial product of a lane's 16 bytes never unpacks the 16-bit types: q stays in its stored
+// form and v_dot2 multiplies two pairs per instruction into an fp32 sum (products of 16-bit floats are
+// exact in fp32); the score scale is applied to the finished dot product (kPostScale).  fp32 rows use
+// plain FMAs against a q that was scaled once up front.
 struct F32 {
   static constexpr int kBytes = 4, kPerVec = 4;
+  static constexpr bool kPostScale = false;
+  struct Q {
+    float f[4];
+  };
   static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -92,9 +102,26 @@ struct F32 {
       f[i] = __builtin_bit_cast(float, w);
     }
   }
+  static __device__ __forceinline__ Q make_q(const u32x4& r, float scale) {
+    Q q;
+    unpack(r, q.f);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) q.f[i] *= scale;
+    return q;
+  }
+  static __device__ __forceinline__ float dot(const u32x4& k, const Q& q) {
+    float kf[4];
+    unpack(k, kf);
+    float d = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) d = fmaf(kf[i], q.f[i], d);
+    return d;
+  }
 };
 struct F16 {
   static constexpr int kBytes = 2, kPerVec = 8;
+  static constexpr bool kPostScale = true;
+  typedef u32x4 Q;
   static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -104,9 +131,21 @@ struct F16 {
       f[2 * i + 1] = (float)h.y;
     }
   }
+  static __device__ __forceinline__ Q make_q(const u32x4& r, float) { return r; }
+  static __device__ __forceinline__ float dot(const u32x4& k, const Q& q) {
+    float d = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t kw = k[i], qw = q[i];
+      d = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, kw), __builtin_bit_cast(f16x2, qw), d, false);
+    }
+    return d;
+  }
 };
 struct BF16 {
   static constexpr int kBytes = 2, kPerVec = 8;
+  static constexpr bool kPostScale = true;
+  typedef u32x4 Q;
   static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -114,6 +153,16 @@ struct BF16 {
       f[2 * i] = __builtin_bit_cast(float, w << 16);
       f[2 * i + 1] = __builtin_bit_cast(float, w & 0xffff0000u);
     }
+  }
+  static __device__ __forceinline__ Q make_q(const u32x4& r, float) { return r; }
+  static __device__ __forceinline__ float dot(const u32x4& k, const Q& q) {
+    float d = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t kw = k[i], qw = q[i];
+      d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kw), __builtin_bit_cast(bf16x2, qw), d, false);
+    }
+    return d;
   }
 };
 
@@ -241,15 +290,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   // not exist (q_len not a multiple of NQ) computes them from the last real one and never writes them.
   const int nq_here = min(NQ, a.q_len - a.q_first);
   auto qrow = [&](int j) { return ((size_t)b * a.q_len + (size_t)(a.q_first + min(j, nq_here - 1))) * a.heads + h; };
-  // q pieces of this lane, pre-multiplied by scale*log2(e) so that exp() becomes exp2().
-  float qf[NQ][EPL];
+  // q pieces of this lane.  Scores carry the factor scale*log2(e), so that exp() becomes exp2(): fp32 q is
+  // multiplied by it here, 16-bit q stays as stored and the finished dot product is multiplied instead.
+  typename Elt::Q qv[NQ];
 #pragma unroll
   for (int j = 0; j < NQ; ++j) {
     const u32x4 qr = *reinterpret_cast<const u32x4*>((const char*)a.q + qrow(j) * ROWB + (uint32_t)lir * 16u);
-    Elt::unpack(qr, qf[j]);
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) qf[j][i] *= a.scale_log2e;
+    qv[j] = Elt::make_q(qr, a.scale_log2e);
   }
+  const float post = Elt::kPostScale ? a.scale_log2e : 1.f;
   // Causal limit (few-query variant): query token j sees no position after its own, q_pos[b] + q_first + j.
   int lim[NQ];
 #pragma unroll
@@ -407,13 +456,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     bool mine = false;
     for (int r = lane; r < wn; r += 64) mine = mine || (kDense ? vrow(w0 + r) : s_pos[wave][r]) == new_pos;
     if (__builtin_amdgcn_ballot_w64(mine) != 0) {  // wave-uniform
-      float kf[EPL], vf[EPL];
-      Elt::unpack(s_new[wave][0][lir], kf);
+      float vf[EPL];
       Elt::unpack(s_new[wave][1][lir], vf);
-      float d = 0.f;
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[0][i], d);
-      d = group_allreduce_sum<LPR>(d);
+      const float d = group_allreduce_sum<LPR>(Elt::dot(s_new[wave][0][lir], qv[0])) * post;
       if (grp == 0) {
         const float l_one = 1.f;
         merge_state(m[0], l[0], acc[0], EPL, d, l_one, vf);
@@ -445,14 +490,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     float w[NQ][U];  // scores first, then softmax weights
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float kf[EPL];
-      Elt::unpack(kr[u], kf);
 #pragma unroll
       for (int j = 0; j < NQ; ++j) {
-        float d = 0.f;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) d = fmaf(kf[i], qf[j][i], d);
-        d = group_allreduce_sum<LPR>(d);
+        const float d = group_allreduce_sum<LPR>(Elt::dot(kr[u], qv[j])) * post;
         w[j][u] = (ok[u] && (NQ == 1 || pos[u] <= lim[j])) ? d : -INFINITY;
       }
     }

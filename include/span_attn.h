@@ -152,6 +152,22 @@ int dense_decode_attn_append(const span_attn_desc_t* desc, const void* q, const 
                              float scale, float* out);
 
 /*
+ * The step between two decode steps of one group of tokens.  Anchors and references are generated
+ * once per group (Sec. 3.2 "Overhead"), so the span is chosen per group: from one token of the group to
+ * the next it only gains the token just decoded.  For every sequence b, with p = append_pos[b] the
+ * position that token was appended at, on desc->stream:
+ *    if position p is in the span and p + 1 is not, the interval ending at p + 1 now ends at p + 2
+ *    (the next token will attend itself; its row arrives with the next *_append call);
+ *    append_pos[b] = p + 1;  ctx_lens[b] += 1 when ctx_lens is not NULL.
+ * Sequences with p < 0 or p + 1 >= max_len (cache full) are left untouched.  All pointers are device
+ * memory and are the arrays the next span_decode_attn_append / dense_decode_attn_append call reads, so
+ * a decode loop over the group needs no host work between tokens and the pair of calls can be recorded
+ * into one HIP graph.  desc supplies batch, max_len, num_intervals and stream.
+ */
+int span_advance(const span_attn_desc_t* desc, const int32_t* span_offsets, const int32_t* span_starts,
+                 int32_t* span_ends, int32_t* append_pos, int32_t* ctx_lens);
+
+/*
  * Span-list validation on the HOST (all pointers are host memory; pure CPU).
  * Sequences are scanned in index order; for a sequence its offsets are checked first, then its
  * intervals in list order, each against the rules in this order; the first failure is returned,

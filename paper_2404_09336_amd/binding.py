@@ -62,6 +62,8 @@ def load_library():
         lib.span_decode_attn_append.restype = ctypes.c_int
         lib.dense_decode_attn_append.argtypes = [DP, P, P, P, P, P, P, P, F, P]
         lib.dense_decode_attn_append.restype = ctypes.c_int
+        lib.span_advance.argtypes = [DP, P, P, P, P, P]
+        lib.span_advance.restype = ctypes.c_int
         lib.span_validate.argtypes = [I32, I32, P, P, P, P, P, P, P]
         lib.span_validate.restype = ctypes.c_int
         lib.span_plan_query.argtypes = [DP, ctypes.POINTER(PlanInfo)]
@@ -126,6 +128,25 @@ def span_workspace_init(desc: _Desc) -> None:
     rc = load_library().span_workspace_init(ctypes.byref(desc))
     if rc != 0:
         raise SpanAttnError(rc, "span_workspace_init")
+
+
+def prepare_span_advance(span_offsets, span_starts, span_ends, append_pos, ctx_lens=None, *, max_len, stream=None):
+    """Device int32 tensors; span_ends, append_pos and ctx_lens (optional) are updated in place on the GPU."""
+    import torch
+    lib = load_library()
+    batch, n_int = int(append_pos.numel()), int(span_starts.numel())
+    if stream is None:
+        stream = torch.cuda.current_stream(append_pos.device).cuda_stream
+    desc = make_desc(batch, 1, 64, int(max_len), SPAN_F32, n_int, stream=stream)
+    args = (ctypes.byref(desc), _i32_dev(span_offsets, batch + 1, "span_offsets"), _i32_dev(span_starts, n_int, "span_starts"),
+            _i32_dev(span_ends, n_int, "span_ends"), _i32_dev(append_pos, batch, "append_pos"),
+            _i32_dev(ctx_lens, batch, "ctx_lens") if ctx_lens is not None else None)
+    keep = (span_offsets, span_starts, span_ends, append_pos, ctx_lens)
+    return PreparedCall("span_advance", lib.span_advance, desc, args, None, keep)
+
+
+def span_advance(span_offsets, span_starts, span_ends, append_pos, ctx_lens=None, *, max_len, stream=None):
+    prepare_span_advance(span_offsets, span_starts, span_ends, append_pos, ctx_lens, max_len=max_len, stream=stream)()
 
 
 def span_validate(span_offsets, span_starts, span_ends, ctx_lens):

@@ -653,6 +653,27 @@ __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, size_t n) 
   if (i < n) p[i] = 0u;
 }
 
+// One thread per sequence: the span gains the position after the one just appended (see span_advance).
+__global__ __launch_bounds__(256) void advance_kernel(int batch, int max_len, int num_intervals, const int32_t* offsets,
+                                                      const int32_t* starts, int32_t* ends, int32_t* append_pos,
+                                                      int32_t* ctx_lens) {
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b >= batch) return;
+  const int p = append_pos[b];
+  if (p < 0 || p + 1 >= max_len) return;
+  const int lo = clampi(offsets[b], 0, num_intervals), hi = clampi(offsets[b + 1], lo, num_intervals);
+  int grow = -1;        // interval that ends right after p
+  bool taken = false;   // p + 1 is already inside some interval
+  for (int i = lo; i < hi; ++i) {
+    const int st = starts[i], en = ends[i];
+    if (st < en && en == p + 1) grow = i;
+    if (st <= p + 1 && p + 1 < en) taken = true;
+  }
+  if (grow >= 0 && !taken) ends[grow] = p + 2;
+  append_pos[b] = p + 1;
+  if (ctx_lens) ctx_lens[b] += 1;
+}
+
 thread_local int g_last_hip_error = 0;
 
 template <class Elt, int D, bool kDense, int NQ>
@@ -795,6 +816,22 @@ extern "C" int dense_decode_attn_append(const span_attn_desc_t* desc, const void
   if (!k_new || !v_new || !append_pos) return SPAN_ERR_NULL;
   return spanattn::launch<true>(desc, q, k_cache, v_cache, nullptr, nullptr, nullptr, ctx_lens, scale, out, k_new,
                                 v_new, append_pos);
+}
+
+extern "C" int span_advance(const span_attn_desc_t* desc, const int32_t* span_offsets, const int32_t* span_starts,
+                            int32_t* span_ends, int32_t* append_pos, int32_t* ctx_lens) {
+  const int rc = spanattn::check_desc(desc);
+  if (rc != SPAN_OK) return rc;
+  if (!span_offsets || !append_pos || (desc->num_intervals > 0 && (!span_starts || !span_ends))) return SPAN_ERR_NULL;
+  hipLaunchKernelGGL(spanattn::advance_kernel, dim3((unsigned)((desc->batch + 255) / 256)), dim3(256), 0,
+                     (hipStream_t)desc->stream, desc->batch, desc->max_len, desc->num_intervals, span_offsets,
+                     span_starts, span_ends, append_pos, ctx_lens);
+  const hipError_t err = hipGetLastError();
+  if (err != hipSuccess) {
+    spanattn::g_last_hip_error = (int)err;
+    return SPAN_ERR_HIP;
+  }
+  return SPAN_OK;
 }
 
 extern "C" int span_workspace_init(const span_attn_desc_t* desc) {

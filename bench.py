@@ -86,6 +86,32 @@ class Workload:
         self.partition = (self.plan["max_splits"], self.plan["slice_tokens"], self.plan["workgroups"])
 
 
+def few_query_table(wl, device, steps, single_us):
+    """The few-query entry point on the same workload: q_len new tokens per sequence share one pass over the span
+    (each under its causal limit).  Reports the time per call and per token next to the one-token call."""
+    import numpy as np
+    import torch
+    import paper_2404_09336_amd as span
+    from workloads import draw_queries
+    cfg, table = wl.cfg, {}
+    for q_len in (2, 4, 8):
+        calls = []
+        for c, one in enumerate(wl.span_calls):
+            _, K, V, off, st, en, ctx, _ = one._keepalive
+            q = draw_queries(cfg, q_len, seed=cfg.seed(c), device=device)
+            q_pos = (ctx - q_len).to(torch.int32)            # the new tokens are the last q_len cache rows
+            calls.append(span.prepare_span_decode_attn_multi(q, K, V, off, st, en, q_pos, np.float32(cfg.scale),
+                                                             max_tokens=one.desc.max_tokens,
+                                                             tokens_per_seq=getattr(one.desc, "_tokens_keepalive", None)))
+        r = timed_loop(calls, wl.span_bytes, steps, max(5, steps // 10))
+        us = r["us_per_call_event"]
+        table[f"q_len_{q_len}"] = {"us_per_call": round(us, 2), "us_per_token": round(us / q_len, 2),
+                                   "tokens_per_s": round(cfg.batch * q_len / us * 1e6, 0),
+                                   "speedup_per_token_vs_one_query": round(single_us * q_len / us, 3),
+                                   "passes_over_span": -(-q_len // 4)}
+    return table
+
+
 def auto_copies(cfg_id):
     """Enough copies that the span bytes touched in one rotation are >= 2x the last-level cache."""
     import numpy as np
@@ -283,6 +309,8 @@ def main():
         out["hot_cache_gbps_not_counted"] = round(res_hot["gbps_wall"], 2)
 
     if args.others:
+        if res_span:
+            out["few_query"] = few_query_table(wl, device, max(20, args.steps // 4), res_span["us_per_call_event"])
         table = {}
         for cid in (2, 4, 5):
             del wl

@@ -28,6 +28,8 @@
 //     so the whole call is a single launch.
 //   * the append entry points also write the new token's K / V row into the cache; within that launch
 //     the row is taken from the arguments, never read back from the cache.
+//   * the few-query entry point serves 2 or 4 query tokens of a sequence with one pass over the span's rows
+//     (template argument NQ): per-token softmax states in registers, each token under its own causal limit.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>

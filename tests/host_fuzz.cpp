@@ -175,6 +175,7 @@ static void fuzz_plan() {
     d.num_intervals = rnd(0, 100);
     d.max_tokens = rnd(0, 2) ? 0 : rnd(1, d.max_len);
     d.num_splits = rnd(0, 3) ? 0 : rnd(1, 70000);
+    d.q_len = rnd(0, 2) ? 0 : rnd(1, 64);
     std::vector<int64_t> tok(d.batch);
     for (auto& t : tok) t = rnd(0, 9) == 0 ? rnd(-5, 0) : rnd(0, d.max_len + 10);
     d.tokens_per_seq = rnd(0, 1) ? tok.data() : nullptr;
@@ -182,6 +183,7 @@ static void fuzz_plan() {
     REQUIRE(span_plan_query(&d, &info) == SPAN_OK);
     const spanattn::Partition p = spanattn::plan_partition(&d, table.data());
     REQUIRE(p.num_splits >= 1 && p.slice_tokens >= 1 && p.total_slices >= 1);
+    REQUIRE(p.queries_per_pass == (d.q_len >= 3 ? 4 : (d.q_len == 2 ? 2 : 1)));
     REQUIRE(info.workspace_bytes == (int64_t)span_workspace_bytes(&d));
     if (p.exact) {
       REQUIRE(p.total_slices <= spanattn::kMaxPlanSlices);

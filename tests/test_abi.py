@@ -119,6 +119,26 @@ def test_partition_arithmetic_exact():
                                                       tokens_per_seq=np.ones(1025)))["exact"]
 
 
+def test_partition_follows_the_query_token_count():
+    """One resident round is 2048 workgroups for one query token, 1536 for two, 1024 for three or more; the
+    workspace grows with the tokens one pass serves (1, 2 or 4), never with q_len itself."""
+    tok = np.full(8, 4096)
+    plans = {}
+    for q_len in (0, 1, 2, 3, 4, 8, 64):
+        d = binding.make_desc(8, 32, 128, 4096, 1, 10, 4096, 0, tokens_per_seq=tok, q_len=q_len)
+        plans[q_len] = span.span_plan_query(d)
+    assert plans[0] == plans[1]
+    assert plans[1]["workgroups"] == 2048 and plans[2]["workgroups"] == 1536 and plans[4]["workgroups"] == 1024
+    assert plans[3] == plans[4] == plans[8] == plans[64]
+    per_slot = lambda pl: (pl["workspace_bytes"] - 256) / pl["workgroups"]       # 256 B of counters at this size
+    assert abs(per_slot(plans[1]) - 130 * 4) < 1 and abs(per_slot(plans[2]) - 2 * 130 * 4) < 1
+    assert abs(per_slot(plans[4]) - 4 * 130 * 4) < 1
+    for bad in (-1, 65):
+        d = binding.make_desc(8, 32, 128, 4096, 1, 10, 4096, 0, q_len=bad)
+        with pytest.raises(span.SpanAttnError):
+            span.span_plan_query(d)
+
+
 def test_validator_matches_oracle_on_golden_cases():
     for ctx, off, st, en, exp in load_golden():
         got = span.span_validate(off, st, en, ctx)

@@ -27,7 +27,8 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"span_decode_attn", "dense_decode_attn", "span_validate", "span_plan_query", "span_workspace_bytes",
             "span_workspace_init", "span_strerror", "span_last_hip_error", "span_blocks_to_intervals",
-            "span_intervals_to_blocks", "span_build", "span_decode_attn_append", "dense_decode_attn_append"} <= set(names)
+            "span_intervals_to_blocks", "span_build", "span_decode_attn_append", "dense_decode_attn_append",
+            "span_decode_attn_multi", "span_advance"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
@@ -68,6 +69,29 @@ def test_argument_errors_are_reported_before_any_launch():
     lib = span.load_library()
     assert lib.dense_decode_attn(ctypes.byref(mk()), 1, 1, 1, None, 0.1, 1) == -1
     assert lib.dense_decode_attn(ctypes.byref(mk(head_dim=32)), 1, 1, 1, 1, 0.1, 1) == -2
+
+
+def test_argument_errors_of_the_few_query_and_advance_calls():
+    """All of these return before any launch (the pointers are fakes)."""
+    lib = span.load_library()
+    mk = lambda **kw: binding.make_desc(**{**dict(batch=2, heads=4, head_dim=128, max_len=64, dtype_code=1,
+                                                  num_intervals=4, q_len=3), **kw})
+    P = ctypes.c_void_p
+    multi = lambda d, q=1, off=1, out=1: lib.span_decode_attn_multi(
+        ctypes.byref(d), P(q) if q else None, P(1), P(1), P(off) if off else None, P(1), P(1), None, 0.1,
+        P(out) if out else None)
+    assert multi(mk(), q=0) == -1 and multi(mk(), off=0) == -1 and multi(mk(), out=0) == -1
+    assert multi(mk(q_len=65)) == -2 and multi(mk(q_len=-1)) == -2 and multi(mk(head_dim=32)) == -2
+    assert multi(mk(num_splits=2)) == -4                       # several slices need a workspace
+    # every other entry point takes one query token only
+    assert _call_span(mk()) == -2
+    assert lib.dense_decode_attn(ctypes.byref(mk()), 1, 1, 1, 1, 0.1, 1) == -2
+    assert lib.span_decode_attn_append(ctypes.byref(mk()), 1, 1, 1, 1, 1, 1, 1, 1, 1, 0.1, 1) == -2
+    adv = lambda d, off=1, en=1, pos=1: lib.span_advance(ctypes.byref(d) if d is not None else None,
+                                                         P(off) if off else None, P(1), P(en) if en else None,
+                                                         P(pos) if pos else None, None)
+    assert adv(None) == -1 and adv(mk(), off=0) == -1 and adv(mk(), en=0) == -1 and adv(mk(), pos=0) == -1
+    assert adv(mk(batch=0)) == -2
 
 
 def test_partition_arithmetic_uniform():

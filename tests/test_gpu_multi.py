@@ -147,3 +147,35 @@ def test_single_query_entry_points_reject_several_tokens(gpu_device):
     rc = lib.span_decode_attn_multi(ctypes.byref(d), q.data_ptr(), K.data_ptr(), V.data_ptr(), off.data_ptr(),
                                     st.data_ptr(), en.data_ptr(), None, 0.1, out.data_ptr())
     assert rc == -2
+
+
+@pytest.mark.parametrize("seed", list(range(18)))
+def test_multi_random_shapes_and_lists(seed, gpu_device):
+    """Random shapes, list structures (up to 90 intervals, single positions, long runs), token counts, limits and
+    slicing modes; the case is printed before it runs."""
+    from workloads import place_disjoint
+    rng = np.random.default_rng(3000 + seed)
+    dtype = ["f16", "bf16", "f32"][seed % 3]
+    D = [128, 64][(seed // 3) % 2]
+    B, H = int(rng.integers(1, 6)), int(rng.choice([1, 3, 8, 32]))
+    L = int(rng.choice([40, 300, 1500, 5000]))
+    q_len = int(rng.integers(1, 10))
+    cfg = DecodeConfig(300 + seed, "random-multi", B, H, D, L, L, dtype, TOL[dtype])
+    ctx = rng.integers(q_len + 1, L + 1, size=B).astype(np.int32)
+    per_seq = []
+    for b in range(B):
+        n = int(ctx[b])
+        k = int(rng.integers(1, min(n, 90) + 1))
+        style = rng.integers(0, 3)
+        hi = 1 if style == 0 else (max(1, n // k) if style == 1 else max(1, min(n // k, 7)))
+        per_seq.append(place_disjoint(rng, rng.integers(1, hi + 1, size=k), 0, n))
+    sp = SpanBatch.from_lists(per_seq, ctx)
+    limit_style = seed % 3          # tokens at the end of the cache / anywhere (also before the span) / no limit
+    q_pos = [(ctx - q_len).astype(np.int32), rng.integers(-3, L, size=B).astype(np.int32), None][limit_style]
+    kw = [dict(), dict(tokens_per_seq=None), dict(num_splits=int(rng.integers(1, 9)), tokens_per_seq=None)][(seed // 3) % 3]
+    print(f"[case] seed {seed}: {dtype} D={D} B={B} H={H} L={L} q_len={q_len} ctx={ctx.tolist()} "
+          f"intervals={[len(p) for p in per_seq]} q_pos={None if q_pos is None else q_pos.tolist()} kw={kw}", flush=True)
+    _, K, V = draw_qkv(cfg, ctx, device=gpu_device, seed=seed)
+    q = draw_queries(cfg, q_len, device=gpu_device)
+    check(run_multi(cfg, sp, q, K, V, q_pos, gpu_device, **kw), oracle_multi(cfg, sp, q, K, V, q_pos), cfg.tol,
+          f"random few-query case {seed}")

@@ -13,6 +13,7 @@ constexpr int kWavesPerBlock = 4;          // 256 threads per workgroup
 constexpr int kMaxSlice = 1 << 22;         // a slice may be a whole sequence (positions are tabulated window by window)
 constexpr int kMinSlice = 128;             // do not cut work finer than this many positions
 constexpr int kSliceGranule = 16;
+constexpr int kUnsplitFromPairs = 512;     // level batches with at least this many (batch, head) pairs are not sliced
 constexpr int kLargeSlice = 1024;          // slices above this size are cut down to it, in several rounds of workgroups
 constexpr int kMaxLen = 1 << 22;           // keeps every in-slab byte offset inside 32 bits
 constexpr int64_t kTargetWorkgroups = 2048;  // 256 CUs x 8 resident workgroups

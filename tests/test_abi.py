@@ -163,6 +163,21 @@ def test_partition_follows_the_query_token_count():
             span.span_plan_query(d)
 
 
+def test_level_batches_with_enough_pairs_are_not_sliced():
+    """At least 512 (batch, head) pairs and the longest sequence within 35 % of the mean: one workgroup per pair."""
+    rng = np.random.default_rng(8)
+    tok = rng.integers(420, 560, size=16)
+    level = binding.make_desc(16, 32, 128, 4096, 1, 16, int(tok.max()), 0, tokens_per_seq=tok)
+    plan = span.span_plan_query(level)
+    assert plan["max_splits"] == 1 and plan["workgroups"] == 512 and plan["workspace_bytes"] == 0
+    ragged = tok.copy()
+    ragged[0] = 1100                                             # one long sequence: slices level the work again
+    plan = span.span_plan_query(binding.make_desc(16, 32, 128, 4096, 1, 16, 1100, 0, tokens_per_seq=ragged))
+    assert plan["max_splits"] > 1 and plan["workgroups"] > 1024
+    few = binding.make_desc(8, 32, 128, 4096, 1, 16, int(tok.max()), 0, tokens_per_seq=tok[:8])   # 256 pairs
+    assert span.span_plan_query(few)["max_splits"] > 1
+
+
 def test_validator_matches_oracle_on_golden_cases():
     for ctx, off, st, en, exp in load_golden():
         got = span.span_validate(off, st, en, ctx)

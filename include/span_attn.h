@@ -19,7 +19,8 @@
  *   - Return value: 0 = OK; negative = argument / runtime error found on the host before
  *     anything was launched (SPAN_ERR_*); positive = span-list validation class
  *     (SPAN_BAD_*, only from span_validate).  Nothing throws or aborts across this ABI.
- *   - Layouts, all contiguous: q and out [batch, heads, head_dim]; k_cache and v_cache
+ *   - Layouts, all contiguous: q and out [batch, heads, head_dim] ([batch, q_len, heads, head_dim]
+ *     for span_decode_attn_multi); k_cache and v_cache
  *     [batch, heads, max_len, head_dim] (a KV cache pre-allocated to its maximum length, Sec. 4),
  *     so an interval of n positions is one run of n*head_dim elements per (batch, head).
  *   - out is always fp32, whatever the input type.
@@ -39,7 +40,8 @@ typedef enum { SPAN_F32 = 0, SPAN_F16 = 1, SPAN_BF16 = 2 } span_dtype_t;
 enum {
   SPAN_OK = 0,
   SPAN_ERR_NULL = -1,      /* a required pointer is NULL                                       */
-  SPAN_ERR_SHAPE = -2,     /* non-positive dimension, head_dim not 64 / 128, max_len > 2^22    */
+  SPAN_ERR_SHAPE = -2,     /* non-positive dimension, head_dim not 64 / 128, max_len > 2^22,
+                              q_len outside what the entry point takes                         */
   SPAN_ERR_DTYPE = -3,     /* dtype is not a span_dtype_t                                      */
   SPAN_ERR_WORKSPACE = -4, /* workspace missing, misaligned (256 B) or smaller than required   */
   SPAN_ERR_HIP = -5,       /* a HIP call failed; see span_last_hip_error()                     */

@@ -378,3 +378,23 @@ def test_largest_supported_cache_length(gpu_device):
     assert lib.span_workspace_bytes(d) == 0 and span.span_strerror(-2)        # one row more is refused
     with pytest.raises(span.SpanAttnError):
         span.span_plan_query(d)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_large_and_tiny_scores(dtype, gpu_device):
+    """Scores far outside exp's comfortable range: peaky softmax (|s| in the hundreds), all scores hugely
+    negative, all scores ~0 with subnormal inputs.  Only differences of scores matter (eq. (5)); nothing may
+    overflow, underflow to 0/0 or turn into NaN, with one slice or several."""
+    cfg = small_cfg(dtype, 128, B=3, H=4, L=900, min_len=900)
+    sp = SpanBatch.from_lists([[(0, 40), (300, 700)], [(5, 6)], [(100, 900)]], [900, 900, 900])
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=11)
+    cases = {
+        "peaky": (q * 12, K * 6),                                   # scores ~ N(0, 72 * sqrt(128)) * scale
+        "all very negative": (q.abs() * 20, -K.abs() * 20),          # every product negative: scores ~ -3e3
+        "tiny": (q * 1e-4, K * 1e-4 if dtype != "f16" else K * 1e-3),   # fp16: K * 1e-3 is partly subnormal
+    }
+    for name, (qq, KK) in cases.items():
+        qq, KK = qq.to(q.dtype).contiguous(), KK.to(K.dtype).contiguous()
+        ref = oracle_span(cfg, sp, qq, KK, V)
+        for kw in (dict(), dict(num_splits=5, tokens_per_seq=None)):
+            check(run_span(cfg, sp, qq, KK, V, gpu_device, **kw), ref, cfg.tol, f"{dtype} {name} {kw}")

@@ -304,7 +304,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   // Causal limit (few-query variant): query token j sees no position after its own, q_pos[b] + q_first + j.
   int lim[NQ];
 #pragma unroll
-  for (int j = 0; j < NQ; ++j) lim[j] = a.q_pos ? a.q_pos[b] + a.q_first + j : 0x7fffffff;
+  for (int j = 0; j < NQ; ++j)  // (clamped: any q_pos at or beyond the cache length means "no limit", without overflow)
+    lim[j] = a.q_pos ? min(a.q_pos[b], kMaxLen) + a.q_first + j : 0x7fffffff;
 
   // ---- step 1: how many attended positions does the sequence have, which are mine ----------------
   // with fixed-size slices the count may stop at the slice's end; even slices need the sequence's total

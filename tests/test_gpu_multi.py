@@ -98,7 +98,7 @@ def test_multi_limit_cases(gpu_device):
     sp = SpanBatch.from_lists(per_seq, ctx)
     _, K, V = draw_qkv(cfg, ctx, device=gpu_device)
     q = draw_queries(cfg, 4, device=gpu_device)
-    q_pos = np.array([5, 8, 48, 100, 598], np.int32)   # nothing / first rows appear / interval end / gap / all
+    q_pos = np.array([5, 8, 48, 100, 2**31 - 1], np.int32)   # nothing / first rows appear / interval end / gap / all (no overflow)
     ref = oracle_multi(cfg, sp, q, K, V, q_pos)
     got = run_multi(cfg, sp, q, K, V, q_pos, gpu_device)
     check(got, ref, cfg.tol, "limit cases")

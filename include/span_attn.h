@@ -143,7 +143,7 @@ int dense_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k
  *   k_new, v_new : device, desc->dtype, [batch, heads, head_dim]
  *   append_pos   : device int32 [batch]; a value outside [0, max_len) appends nothing for that sequence
  * The span (or ctx_lens) is expected to cover append_pos[b] - the new token attends to itself - but need
- * not.  Within the launch the row is taken from k_new / v_new, never re-read from the cache, so the
+ * not; the row is appended even for a sequence that attends nothing.  Within the launch the row is taken from k_new / v_new, never re-read from the cache, so the
  * result does not depend on when the store lands; the cache holds the row when the call's work completes.
  */
 int span_decode_attn_append(const span_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,

@@ -271,7 +271,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   // Append variant.  Every lane fetches its piece of the new token's K / V row right away (the latency
   // hides behind the metadata chain).  The row is written into the cache by the first slice's workgroup
   // of each (batch, head) and, in this launch, never read back from the cache: the wave that meets
-  // position new_pos in its rows takes it from these registers instead, so the kernel has no race.
+  // position new_pos in its rows takes it from the copy parked in LDS instead, so the kernel has no race.
   const int new_pos = a.append_pos ? a.append_pos[b] : -2;  // -2 matches no position
   u32x4 kn_raw = {0u, 0u, 0u, 0u}, vn_raw = {0u, 0u, 0u, 0u};
   if (a.append_pos) {
@@ -345,6 +345,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     L[j] = 0.f;
     o[j] = 0.f;
   }
+  // Append variant: the first slice's workgroup writes the new row into the cache, whatever the span holds.
+  if (a.append_pos && split == 0 && wave == 0 && lane < LPR && new_pos >= 0 && new_pos < a.max_len) {
+    const size_t row = (bh * (size_t)a.max_len + (size_t)new_pos) * ROWB + (uint32_t)lir * 16u;
+    *reinterpret_cast<u32x4*>((char*)a.k + row) = kn_raw;
+    *reinterpret_cast<u32x4*>((char*)a.v + row) = vn_raw;
+  }
   if (cnt > 0) {  // same decision in all 4 waves
   // How the slice's rows are dealt to the 4 waves.  My rows are numbered r = 0..nrows-1; row r is
   // virtual token vrow(r) of the sequence.
@@ -386,16 +392,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     for (int i = 0; i < EPL; ++i) acc[j][i] = 0.f;
   }
 
-  if (a.append_pos) {
-    if (lane < LPR) {  // park the new row in LDS (frees the registers); the first slice also writes the cache
-      s_new[wave][0][lane] = kn_raw;
-      s_new[wave][1][lane] = vn_raw;
-      if (split == 0 && wave == 0 && new_pos >= 0 && new_pos < a.max_len) {
-        const size_t row = (bh * (size_t)a.max_len + (size_t)new_pos) * ROWB + lane_off;
-        *reinterpret_cast<u32x4*>((char*)a.k + row) = kn_raw;
-        *reinterpret_cast<u32x4*>((char*)a.v + row) = vn_raw;
-      }
-    }
+  if (a.append_pos && lane < LPR) {  // park the new row in LDS (frees the registers)
+    s_new[wave][0][lane] = kn_raw;
+    s_new[wave][1][lane] = vn_raw;
   }
 
   // ---- step 2: virtual token -> KV position for a window's rows (span path only) -----------------

@@ -110,3 +110,39 @@ def test_append_at_workload_scale(gpu_device):
     print(f"[parity] append at config 3 scale: max-abs err {err:.3e}")
     assert err <= cfg.tol
     assert np.array_equal(_bits(K), _bits(K_ref))
+
+
+def test_append_happens_even_when_nothing_is_attended(gpu_device):
+    """A sequence whose span is empty (the validator would flag it) or whose ctx_len is 0 gets an all-zero output
+    row, and its new K / V row is in the cache all the same."""
+    B, H, D, L = 3, 3, 128, 64
+    cfg = DecodeConfig(97, "append-empty", B, H, D, L, L, "f16", 2e-3)
+    q, K, V = draw_qkv(cfg, np.array([20, 20, 20], np.int32), device=gpu_device, seed=45)
+    g = torch.Generator(device=gpu_device).manual_seed(46)
+    k_new = torch.randn((B, H, D), generator=g, device=gpu_device).half()
+    v_new = torch.randn((B, H, D), generator=g, device=gpu_device).half()
+    pos = [20, 20, 20]
+    K_ref, V_ref = _updated(K, k_new, pos), _updated(V, v_new, pos)
+    off = np.array([0, 1, 1, 2], np.int32)                        # sequence 1 has no interval
+    st, en = np.array([0, 5], np.int32), np.array([21, 21], np.int32)
+    for ns in (0, 3):
+        Kc, Vc = K.clone(), V.clone()
+        out = span.span_decode_attn_append(q, k_new, v_new, Kc, Vc, _dev(np.asarray(pos, np.int32), gpu_device),
+                                           _dev(off, gpu_device), _dev(st, gpu_device), _dev(en, gpu_device),
+                                           np.float32(cfg.scale), num_splits=ns)
+        torch.cuda.synchronize()
+        ref = oracle.span_attn(to_host_raw(q), to_host_raw(K_ref), to_host_raw(V_ref), off, st, en,
+                               np.float32(cfg.scale), dtype="f16")
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.array_equal(got[1], np.zeros_like(got[1])) and np.abs(got - ref).max() <= cfg.tol
+        assert np.array_equal(_bits(Kc), _bits(K_ref)) and np.array_equal(_bits(Vc), _bits(V_ref))
+        Kc, Vc = K.clone(), V.clone()
+        ctx = np.array([21, 0, 21], np.int32)                     # dense form: sequence 1 claims no rows
+        out = span.dense_decode_attn_append(q, k_new, v_new, Kc, Vc, _dev(np.asarray(pos, np.int32), gpu_device),
+                                            _dev(ctx, gpu_device), np.float32(cfg.scale), num_splits=ns)
+        torch.cuda.synchronize()
+        ref = oracle.dense_attn(to_host_raw(q), to_host_raw(K_ref), to_host_raw(V_ref), ctx, np.float32(cfg.scale),
+                                dtype="f16")
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.array_equal(got[1], np.zeros_like(got[1])) and np.abs(got - ref).max() <= cfg.tol
+        assert np.array_equal(_bits(Kc), _bits(K_ref)) and np.array_equal(_bits(Vc), _bits(V_ref))

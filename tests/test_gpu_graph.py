@@ -21,7 +21,7 @@ def test_graph_replay_matches_eager_and_oracle(gpu_device):
     off, st, en, ctx = dev(sp.offsets), dev(sp.starts), dev(sp.ends), dev(sp.ctx_lens)
 
     side = torch.cuda.Stream(device=gpu_device)
-    # the workspace is allocated and its ticket counters zeroed BEFORE capture (the init uses a memset)
+    # the workspace is allocated and zeroed before capture here; the next test records the init call itself
     d = binding.make_desc(cfg.batch, cfg.heads, cfg.head_dim, cfg.max_len, 1, int(st.numel()), int(tok.max()), 0,
                           tokens_per_seq=tok)
     ws = torch.zeros(span.span_workspace_bytes(d), dtype=torch.uint8, device=gpu_device)
@@ -61,3 +61,37 @@ def test_graph_replay_matches_eager_and_oracle(gpu_device):
         assert np.abs(got_s - ref_s).max() <= cfg.tol and np.abs(got_d - ref_d).max() <= cfg.tol, replay
         assert np.abs(got_s - eager.cpu().numpy()).max() <= 1e-6
         assert torch.isfinite(junk)
+
+
+def test_workspace_init_inside_a_graph(gpu_device):
+    """span_workspace_init is a kernel launch, so it can be recorded too: a graph that first re-initialises a
+    workspace full of junk and then runs a sliced call gives the eager result on every replay."""
+    cfg = CONFIGS[2]
+    sp = draw_spans(cfg)
+    tok = sp.tokens_per_seq()
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(gpu_device)
+    off, st, en, ctx = dev(sp.offsets), dev(sp.starts), dev(sp.ends), dev(sp.ctx_lens)
+    side = torch.cuda.Stream(device=gpu_device)
+    d = binding.make_desc(cfg.batch, cfg.heads, cfg.head_dim, cfg.max_len, 1, int(st.numel()), int(tok.max()), 0,
+                          tokens_per_seq=tok)
+    ws = torch.full((span.span_workspace_bytes(d),), 0xAB, dtype=torch.uint8, device=gpu_device)
+    out = torch.empty((cfg.batch, cfg.heads, cfg.head_dim), dtype=torch.float32, device=gpu_device)
+    call = span.prepare_span_decode_attn(q, K, V, off, st, en, ctx, np.float32(cfg.scale), out,
+                                         max_tokens=int(tok.max()), tokens_per_seq=tok, workspace=ws,
+                                         stream=side.cuda_stream)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        span.span_workspace_init(call.desc)
+        call()
+    eager = span.span_decode_attn(q, K, V, off, st, en, ctx, np.float32(cfg.scale), max_tokens=int(tok.max()),
+                                  tokens_per_seq=tok)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        ws.fill_(0xCD)                     # junk again between the replays (eager work on the default stream)
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), replay

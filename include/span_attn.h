@@ -1,7 +1,7 @@
 /*
  * span_attn.h — C ABI of the span-restricted decode-attention library for MI355X (gfx950).
  *
- * The operation (paper Sec. 2.1, eqs. (4)-(6), for the single query row of the decoding
+ * The operation (paper Sec. 2.2, eqs. (4)-(6), for the single query row of the decoding
  * phase; Sec. 3.2 "Token generation" and Sec. 3.3 restrict it to the self-selected span):
  *
  *   S_b        = union of the half-open position intervals of sequence b
@@ -21,7 +21,7 @@
  *     (SPAN_BAD_*, only from span_validate).  Nothing throws or aborts across this ABI.
  *   - Layouts, all contiguous: q and out [batch, heads, head_dim] ([batch, q_len, heads, head_dim]
  *     for span_decode_attn_multi); k_cache and v_cache
- *     [batch, heads, max_len, head_dim] (a KV cache pre-allocated to its maximum length, Sec. 4),
+ *     [batch, heads, max_len, head_dim] (a KV cache pre-allocated to its maximum length, Sec. 4 "Hardware and software"),
  *     so an interval of n positions is one run of n*head_dim elements per (batch, head).
  *   - out is always fp32, whatever the input type.
  */
@@ -111,7 +111,7 @@ int span_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_
 /*
  * Few-query variant: desc->q_len consecutive new tokens of every sequence attend in one call, all
  * through the sequence's one span (a span is chosen once per group of tokens, Sec. 3.2, so the tokens
- * of a group share it).  Among themselves the tokens keep the causal mask of Sec. 2.1: query token j
+ * of a group share it).  Among themselves the tokens keep the causal mask of Sec. 2.2: query token j
  * of sequence b attends the span positions p <= q_pos[b] + j and no later one; eqs. (4)-(6) apply to
  * each query row.  Every K / V row of the span is fetched once per pass and serves up to four query
  * tokens; more than four take ceil(q_len / 4) passes.
@@ -129,7 +129,7 @@ int span_decode_attn_multi(const span_attn_desc_t* desc, const void* q, const vo
 
 /*
  * Dense control: the same computation over S_b = [0, ctx_lens[b]) with no span metadata (decode
- * attention as in Sec. 2.1 "Token generation"; plays the role of the dense baseline of Sec. 4).
+ * attention as in Sec. 2.2 "Token generation"; plays the role of the dense baseline of Sec. 4).
  *   ctx_lens : device int32 [batch]; values are clamped to [0, min(max_len, max_tokens)].
  */
 int dense_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
@@ -137,7 +137,7 @@ int dense_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k
 
 /*
  * The two calls above fused with the step that precedes them in a decode loop: appending the new
- * token's K and V rows to the pre-allocated cache (Sec. 2.1 "KV-cache").  In one launch,
+ * token's K and V rows to the pre-allocated cache (Sec. 2.2 "KV-cache").  In one launch,
  *   k_cache[b, h, append_pos[b], :] = k_new[b, h, :]   (same for V)      for every b, h
  *   out = attention over the UPDATED cache (span / dense as above)
  *   k_new, v_new : device, desc->dtype, [batch, heads, head_dim]

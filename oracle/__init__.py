@@ -9,7 +9,7 @@ Two independent formulations live here:
     positions only; also the few-query form (causal limit over the span), the dense
     control, group states + log-sum-exp merge, and the span-list validator.
   * `bruteforce.py` (numpy float64): additive 0 / -inf mask over *all* positions and a
-    full-length softmax, as the mask is defined in Sec. 2.1; small inputs only.
+    full-length softmax, as the mask is defined in Sec. 2.2; small inputs only.
 """
 import ctypes
 import os

@@ -3,7 +3,7 @@
 TEST INFRASTRUCTURE.  Second formulation of the oracle, written from the mask
 definition instead of the span: build the additive mask M over *all* ctx_len positions
 (0 where the position is attended, -inf elsewhere), take the softmax of M + S over the
-whole row, and multiply by all of V (Sec. 2.1, eqs. (4)-(6) and the paragraph on the
+whole row, and multiply by all of V (Sec. 2.2, eqs. (4)-(6) and the paragraph on the
 attention mask).  Every row of K and V is read, so rows outside the span must be finite.
 """
 import numpy as np

@@ -6,11 +6,10 @@
  * constant or helper with the HIP library, and nothing in the HIP library calls it.
  * It is deliberately plain and slow: no blocking, no fusion, no SIMD intrinsics.
  *
- * What it computes (Sec. 2.1 eqs. (4)-(6), restricted to the one query row of the
- * decoding phase, Sec. 2.1 "Token generation"; the additive mask of eq. (5) is 0 on
- * the span and -inf elsewhere, Sec. 3.3 "we compute self-attention only over tokens
- * inside the selected attention span"; Algorithm 1 is the blocked evaluation of the
- * same quantity):
+ * What it computes (Sec. 2.2 eqs. (4)-(6), restricted to the one query row of the
+ * decoding phase, Sec. 2.2 "Token generation"; the additive mask of eq. (5) is 0 on
+ * the span and -inf elsewhere, so the softmax normaliser runs over span positions
+ * only, Sec. 3.3; Algorithm 1 is the blocked evaluation of the same quantity):
  *
  *   S_b      = union_i [starts[i], ends[i])  for i in [offsets[b], offsets[b+1])
  *   s_j      = scale * sum_t q[b,h,t] * K[b,h,j,t]                 j in S_b
@@ -128,7 +127,7 @@ int oracle_span_attn(int B, int H, int D, int max_len, int dtype, const void* q,
 /*
  * Few-query form: Qn query rows per sequence, one per consecutive new token, all sharing the sequence's
  * span.  Query j of sequence b attends the span positions p with p <= q_pos[b] + j: the causal mask of
- * Sec. 2.1 (a token never attends a later one) laid over the span mask of Sec. 3.3; eqs. (4)-(6) then
+ * Sec. 2.2 (a token never attends a later one) laid over the span mask of Sec. 3.3; eqs. (4)-(6) then
  * apply row by row.  q_pos NULL = no causal limit.  q, out: [B, Qn, H, D].
  */
 int oracle_span_attn_multi(int B, int H, int D, int max_len, int dtype, int Qn, const void* q, const void* K,

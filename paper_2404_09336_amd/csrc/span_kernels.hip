@@ -1,7 +1,7 @@
 // Span-restricted single-query (decode) attention for gfx950: the kernel and the C entry points that launch it.
 //
 // What is computed: for every (batch b, head h), softmax over the scores of the positions in the
-// sequence's span only, times the matching V rows (paper Sec. 2.1 eqs. (4)-(6) for one query row,
+// sequence's span only, times the matching V rows (paper Sec. 2.2 eqs. (4)-(6) for one query row,
 // restricted to the span as in Sec. 3.3).  The paper's own kernel visits fixed-size blocks that
 // touch the span and masks inside them (Algorithm 1); here the span is a list of half-open position
 // intervals, so exactly the rows inside the intervals are read and no mask exists.
@@ -468,24 +468,51 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     }
   }
 
+  // Few-query pass: the span rows between the first and the last token's causal limit (at most NQ - 1
+  // positions of a sequence) are seen by the later tokens only.  The streaming loop below serves the rows every
+  // token of the pass sees; these few are taken in here, one at a time, each into the states of exactly the
+  // tokens that see it - a hidden row never meets a token's sums, not even with weight zero (0 * Inf).
+  if constexpr (NQ > 1) {
+    if (a.q_pos) {
+      for (int r0 = 0; r0 < wn; r0 += 64) {
+        const int p = r0 + lane < wn ? s_pos[wave][r0 + lane] : -1;
+        uint64_t todo = __builtin_amdgcn_ballot_w64(p > lim[0] && p <= lim[NQ - 1]);
+        while (todo != 0) {  // wave-uniform
+          const int pb = __builtin_amdgcn_readlane(p, __builtin_ctzll(todo));
+          todo &= todo - 1;
+          const uint32_t off = (uint32_t)pb * ROWB + lane_off;  // every row group fetches the same row
+          const u32x4 kb = load_row_piece(kslab, off), vb = load_row_piece(vslab, off);
+          float vf[EPL];
+          Elt::unpack(vb, vf);
+#pragma unroll
+          for (int j = 1; j < NQ; ++j) {
+            const float d = group_allreduce_sum<LPR>(Elt::dot(kb, qv[j])) * post;
+            if (pb <= lim[j] && grp == 0) {
+              const float l_one = 1.f;
+              merge_state(m[j], l[j], acc[j], EPL, d, l_one, vf);
+            }
+          }
+        }
+      }
+    }
+  }
+
   // ---- step 3: stream the window's K and V rows, online softmax per row group -------------------
   for (int base = 0; base < wn; base += RPL * U) {
     u32x4 kr[U], vr[U];
     bool ok[U];
-    int pos[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = base + u * RPL + grp;
-      ok[u] = r < wn;
-      const int rc = ok[u] ? r : wn - 1;  // a row past the end re-reads the last one with weight 0
-      const int p = kDense ? vrow(w0 + rc) : s_pos[wave][rc];
-      pos[u] = p;
-      // the appended row is not in the cache yet for this launch: request an offset past the slab
-      // (the buffer hardware returns zeros) and give it no weight here; its owner added it above
-      const bool is_new = p == new_pos;
-      ok[u] = ok[u] && !is_new;
-      if (NQ == 1) ok[u] = ok[u] && p <= lim[0];  // one query: its limit is settled here, not per score
-      const uint32_t off = is_new ? 0xfffffff0u : (uint32_t)p * ROWB + lane_off;
+      const int p = kDense ? vrow(w0 + min(r, wn - 1)) : s_pos[wave][min(r, wn - 1)];
+      // Rows that take no part are not fetched at all: a row group past the window's end, the appended row
+      // (not in the cache yet for this launch; its owner added it above), and span rows after the causal
+      // limit of the first query token of the pass (masked positions have no influence, whatever the cache
+      // holds there: Sec. 2.2, mask paragraph; the few rows that only later tokens of the pass see were
+      // taken in above).  They request an offset past the slab instead, for which the buffer hardware
+      // returns zeros, and get no weight.
+      ok[u] = r < wn && p != new_pos && p <= lim[0];
+      const uint32_t off = ok[u] ? (uint32_t)p * ROWB + lane_off : 0xfffffff0u;
       kr[u] = load_row_piece(kslab, off);
       vr[u] = load_row_piece(vslab, off);
     }
@@ -495,7 +522,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
 #pragma unroll
       for (int j = 0; j < NQ; ++j) {
         const float d = group_allreduce_sum<LPR>(Elt::dot(kr[u], qv[j])) * post;
-        w[j][u] = (ok[u] && (NQ == 1 || pos[u] <= lim[j])) ? d : -INFINITY;
+        w[j][u] = ok[u] ? d : -INFINITY;
       }
     }
 #pragma unroll

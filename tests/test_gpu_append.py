@@ -1,4 +1,4 @@
-"""Fused KV-append + attention (the step before the path in a decode loop, Sec. 2.1 "KV-cache"): parity with
+"""Fused KV-append + attention (the step before the path in a decode loop, Sec. 2.2 "KV-cache"): parity with
 the oracle run on the updated cache, and the cache itself bit-exact."""
 import numpy as np
 import pytest

@@ -179,3 +179,76 @@ def test_multi_random_shapes_and_lists(seed, gpu_device):
     q = draw_queries(cfg, q_len, device=gpu_device)
     check(run_multi(cfg, sp, q, K, V, q_pos, gpu_device, **kw), oracle_multi(cfg, sp, q, K, V, q_pos), cfg.tol,
           f"random few-query case {seed}")
+
+
+def _poison(K, V, b, rows, gpu_device):
+    """NaN into K and alternating +Inf / -Inf into V on the given cache rows of sequence b (all heads)."""
+    idx = torch.as_tensor(rows, device=gpu_device, dtype=torch.long)
+    K[b, :, idx] = float("nan")
+    sign = torch.where(idx % 2 == 0, 1.0, -1.0).to(V.dtype)
+    V[b, :, idx] = (sign * float("inf"))[None, :, None].expand(V.shape[1], -1, V.shape[3])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("q_len", [1, 2, 3, 4, 6])
+def test_poisoned_span_rows_past_the_limits_have_no_influence(dtype, D, q_len, gpu_device):
+    """GPU twin of the oracle pin of the same name (masked positions have no influence, Sec. 2.2 mask paragraph).
+    Span rows after the last query token's causal limit hold NaN (K) and +-Inf (V), as an uninitialised
+    pre-allocated cache may: every output row must still equal the oracle's, which never looks at them.  Runs the
+    one-token call with a limit, the 2- and 4-token kernels, padded and multi-pass token counts, unsplit and sliced."""
+    cfg = DecodeConfig(93, "multi-poison", 3, 4, D, 420, 330, dtype, TOL[dtype])
+    rng = np.random.default_rng(500 + q_len)
+    ctx = rng.integers(cfg.min_len, cfg.max_len + 1, size=cfg.batch).astype(np.int32)
+    per_seq, q_pos, hidden = [], [], []
+    for b in range(cfg.batch):
+        n = int(ctx[b])
+        tail = int(rng.integers(40, 90))                      # the recent interval [n - tail, n)
+        per_seq.append([(0, 17), (60 + 11 * b, 150 + 7 * b), (n - tail, n)])
+        p0 = [n - tail + 5, 100 + 7 * b, n - q_len - 9][b]     # limit inside the tail / inside the middle interval / near the end
+        q_pos.append(p0)
+        last_seen = p0 + q_len - 1
+        hidden.append([p for s, e in per_seq[b] for p in range(s, e) if p > last_seen])
+        assert hidden[b], "every sequence needs span rows past its last limit"
+    sp = SpanBatch.from_lists(per_seq, ctx)
+    q_pos = np.array(q_pos, np.int32)
+    _, K, V = draw_qkv(cfg, ctx, seed=cfg.seed() + q_len, device=gpu_device)
+    q = draw_queries(cfg, q_len, device=gpu_device)
+    clean = oracle_multi(cfg, sp, q, K, V, q_pos)
+    for b in range(cfg.batch):
+        _poison(K, V, b, hidden[b], gpu_device)
+    ref = oracle_multi(cfg, sp, q, K, V, q_pos)
+    assert np.array_equal(ref, clean) and np.isfinite(ref).all()      # the oracle does not look at those rows
+    check(run_multi(cfg, sp, q, K, V, q_pos, gpu_device), ref, cfg.tol, f"poisoned {dtype} D={D} q_len={q_len}")
+    check(run_multi(cfg, sp, q, K, V, q_pos, gpu_device, tokens_per_seq=None), ref, cfg.tol,
+          f"poisoned {dtype} D={D} q_len={q_len}, uniform grid")
+    for splits in (2, 5):
+        check(run_multi(cfg, sp, q, K, V, q_pos, gpu_device, num_splits=splits, tokens_per_seq=None), ref, cfg.tol,
+              f"poisoned {dtype} D={D} q_len={q_len}, {splits} slices")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("q_len", [2, 4, 7])
+def test_a_row_only_later_tokens_see_does_not_touch_the_earlier_ones(dtype, q_len, gpu_device):
+    """The row at the last token's own position holds +Inf in V: the last token's output is not finite (in the
+    oracle too), every earlier token's row must equal the oracle's finite result (no 0 * Inf)."""
+    cfg = DecodeConfig(94, "multi-band", 2, 3, 128, 300, 300, dtype, TOL[dtype])
+    ctx = np.full(cfg.batch, 300, np.int32)
+    sp = SpanBatch.from_lists([[(3, 40), (200, 300)], [(0, 9), (120, 180), (250, 300)]], ctx)
+    q_pos = np.array([260, 270], np.int32)
+    _, K, V = draw_qkv(cfg, ctx, device=gpu_device)
+    q = draw_queries(cfg, q_len, device=gpu_device)
+    for b in range(cfg.batch):
+        V[b, :, int(q_pos[b]) + q_len - 1] = float("inf")
+    ref = oracle_multi(cfg, sp, q, K, V, q_pos)
+    assert np.isfinite(ref[:, :q_len - 1]).all() and not np.isfinite(ref[:, q_len - 1]).any()
+    for kw in (dict(), dict(num_splits=3, tokens_per_seq=None)):
+        code, _, _, tok = span.span_validate(sp.offsets, sp.starts, sp.ends, sp.ctx_lens)
+        kw.setdefault("tokens_per_seq", tok)
+        out = span.span_decode_attn_multi(q, K, V, _dev(sp.offsets, gpu_device), _dev(sp.starts, gpu_device),
+                                          _dev(sp.ends, gpu_device), _dev(q_pos, gpu_device), np.float32(cfg.scale),
+                                          max_tokens=int(tok.max()), **kw)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        check(got[:, :q_len - 1], ref[:, :q_len - 1], cfg.tol, f"band row, {dtype} q_len={q_len} {sorted(kw)}")
+        assert not np.isfinite(got[:, q_len - 1]).any()

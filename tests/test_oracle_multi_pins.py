@@ -1,5 +1,5 @@
 """Pins for the few-query form of the fp64 oracle (several new tokens share one span, each under the
-causal mask of Sec. 2.1): library attention with a boolean mask, the brute-force additive mask, the
+causal mask of Sec. 2.2): library attention with a boolean mask, the brute-force additive mask, the
 single-query oracle on clipped spans, and closed forms.  CPU only."""
 import numpy as np
 import torch

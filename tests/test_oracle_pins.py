@@ -1,6 +1,6 @@
 """Pins for the fp64 oracle: everything here runs on the CPU and compares the oracle with
 something that is not the oracle — a library routine, a closed form, brute force, or an
-invariant fixed by the mathematics of Sec. 2.1 eqs. (4)-(6) and Sec. 3.3."""
+invariant fixed by the mathematics of Sec. 2.2 eqs. (4)-(6) and Sec. 3.3."""
 import itertools
 import math
 

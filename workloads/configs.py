@@ -1,7 +1,7 @@
 """The five decode-attention workloads, as shapes only.
 
-Shapes follow the paper's set-up: LLaMA-7B heads (32 x 128, Sec. 2.2 and 4),
-batch sizes 8-64 (Sec. 2.2, 4.1, 4.2), contexts 512-2048 tokens (Sec. 4.1),
+Shapes follow the paper's set-up: LLaMA-7B heads (32 x 128, Sec. 2.3 and 4),
+batch sizes 8-64 (Sec. 2.3, 4.1, 5.2), contexts 512-2048 tokens (Sec. 4.1),
 stretched to 16384 for the stress case.  Config ids are 1-based.
 """
 from dataclasses import dataclass

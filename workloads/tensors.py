@@ -1,7 +1,7 @@
 """Seeded q / K / V tensors in the pre-allocated KV-cache layout.
 
 q: [batch, heads, head_dim]; K, V: [batch, heads, max_len, head_dim], contiguous
-(a per-request cache pre-allocated to its maximum length, Sec. 2.2 and 4).
+(a per-request cache pre-allocated to its maximum length, Sec. 2.3 and Sec. 4 "Hardware and software").
 Values are N(0,1) drawn in fp32 and rounded once to the workload's type; rows at
 positions >= ctx_lens[b] are never valid and are filled with NaN so that any
 read of them shows up in the result.

@@ -46,6 +46,8 @@ enum {
   SPAN_ERR_WORKSPACE = -4, /* workspace missing, misaligned (256 B) or smaller than required   */
   SPAN_ERR_HIP = -5,       /* a HIP call failed; see span_last_hip_error()                     */
   SPAN_ERR_CAPACITY = -6,  /* an output array is too small; the needed size is reported        */
+  SPAN_ERR_SCRATCH_LIMIT = -7, /* span_decode_attn_static: the call needs more scratch than
+                              SPAN_STATIC_SCRATCH_BYTES; use span_decode_attn with a workspace */
   SPAN_BAD_OFFSETS = 1,
   SPAN_BAD_RANGE = 2,
   SPAN_BAD_EMPTY_INTERVAL = 3,
@@ -107,6 +109,26 @@ typedef struct span_attn_desc {
 int span_decode_attn(const span_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
                      const int32_t* span_offsets, const int32_t* span_starts, const int32_t* span_ends,
                      const int32_t* ctx_lens, float scale, float* out);
+
+/*
+ * span_decode_attn for callers that cannot allocate device memory or hand in a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same plan, same
+ * kernels and the same result as span_decode_attn; desc->workspace and desc->workspace_bytes are ignored.
+ * The slices' partial softmax states and tickets go to an array the library itself owns in device memory:
+ * SPAN_STATIC_SCRATCH_BYTES per GPU the library runs on, held until the process ends.  The call allocates
+ * and frees nothing.  If the plan needs more than that (span_workspace_bytes(desc) tells), nothing is
+ * launched and SPAN_ERR_SCRATCH_LIMIT is returned.
+ * The device that owns desc->stream must be the current device.  The first call on a device looks up
+ * where that device's array lives (do it once before a graph capture starts).  Every call clears the
+ * tickets it will use (a small fill kernel on desc->stream ahead of the attention kernel), so the array
+ * may hold anything from earlier calls of any shape.  All calls on one GPU share the one array: two
+ * calls that may overlap in time on the same GPU (different streams, or graphs replayed concurrently)
+ * race and give unspecified results - serialise them, or use span_decode_attn with separate workspaces.
+ */
+#define SPAN_STATIC_SCRATCH_BYTES (4u << 20)
+int span_decode_attn_static(const span_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
+                            const int32_t* span_offsets, const int32_t* span_starts, const int32_t* span_ends,
+                            const int32_t* ctx_lens, float scale, float* out);
 
 /*
  * Few-query variant: desc->q_len consecutive new tokens of every sequence attend in one call, all

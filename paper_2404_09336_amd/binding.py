@@ -54,6 +54,8 @@ def load_library():
         DP = ctypes.POINTER(_Desc)
         lib.span_decode_attn.argtypes = [DP, P, P, P, P, P, P, P, F, P]
         lib.span_decode_attn.restype = ctypes.c_int
+        lib.span_decode_attn_static.argtypes = [DP, P, P, P, P, P, P, P, F, P]
+        lib.span_decode_attn_static.restype = ctypes.c_int
         lib.span_decode_attn_multi.argtypes = [DP, P, P, P, P, P, P, P, F, P]
         lib.span_decode_attn_multi.restype = ctypes.c_int
         lib.dense_decode_attn.argtypes = [DP, P, P, P, P, F, P]
@@ -348,6 +350,35 @@ def prepare_span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, spa
             float(scale), out.data_ptr())
     keep = (q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, workspace)
     return PreparedCall("span_decode_attn", lib.span_decode_attn, desc, args, out, keep)
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def prepare_span_decode_attn_static(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out, *,
+                                    max_tokens=0, num_splits=0, stream=None, tokens_per_seq=None) -> PreparedCall:
+    """span_decode_attn on the library's own scratch array: no workspace is created or passed, `out` is the
+    caller's.  Invoking the prepared call allocates nothing."""
+    import torch
+    lib = load_library()
+    B, H, L, D = _check_qkv(q, k_cache, v_cache)
+    if out is None or out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous() or out.shape != q.shape:
+        raise ValueError("out must be a contiguous fp32 GPU tensor shaped like q")
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    n_int = int(span_starts.numel())
+    desc = make_desc(B, H, D, L, _dtype_code(q), n_int, int(max_tokens), int(num_splits), 0, 0, stream, tokens_per_seq)
+    ctx_p = _i32_dev(ctx_lens, B, "ctx_lens") if ctx_lens is not None else None
+    args = (ctypes.byref(desc), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(),
+            _i32_dev(span_offsets, B + 1, "span_offsets"), _i32_dev(span_starts, n_int, "span_starts"),
+            _i32_dev(span_ends, n_int, "span_ends"), ctx_p, float(scale), out.data_ptr())
+    keep = (q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, out)
+    return PreparedCall("span_decode_attn_static", lib.span_decode_attn_static, desc, args, out, keep)
+
+
+def span_decode_attn_static(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out, **kw):
+    return prepare_span_decode_attn_static(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale,
+                                           out, **kw)()
 
 
 def prepare_dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out=None, *, max_tokens=0, num_splits=0,

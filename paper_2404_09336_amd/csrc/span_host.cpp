@@ -404,6 +404,7 @@ extern "C" const char* span_strerror(int code) {
     case SPAN_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SPAN_ERR_HIP: return "a HIP call failed (see span_last_hip_error)";
     case SPAN_ERR_CAPACITY: return "output array too small (needed size reported)";
+    case SPAN_ERR_SCRATCH_LIMIT: return "the call needs more scratch than the library's static buffer holds";
     case SPAN_BAD_OFFSETS: return "span_offsets must start at 0, not decrease, and stay within num_intervals";
     case SPAN_BAD_RANGE: return "interval outside [0, ctx_len]";
     case SPAN_BAD_EMPTY_INTERVAL: return "interval with start >= end";

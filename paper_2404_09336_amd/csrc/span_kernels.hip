@@ -34,6 +34,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "span_attn.h"
@@ -705,6 +706,38 @@ __global__ __launch_bounds__(256) void advance_kernel(int batch, int max_len, in
 
 thread_local int g_last_hip_error = 0;
 
+// ---- scratch owned by the library, for span_decode_attn_static ---------------------------------------
+// One array per GPU the library runs on, resident until the process ends.  `scratch` is only a host-side
+// handle here: host code never passes it to a kernel or a copy, it asks the runtime once per device where
+// that device's copy lives and uses that address from then on.
+static __device__ __align__(256) unsigned char scratch[SPAN_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, null until first asked
+
+// Address of the current device's scratch array; resolves it on the first call for that device.
+int static_scratch(void** ptr) {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err == hipSuccess && (dev < 0 || dev >= kMaxDevices)) err = hipErrorInvalidDevice;
+  if (err == hipSuccess) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+      void* p = nullptr;
+      err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (err == hipSuccess && (!p || ((uintptr_t)p & 255u))) err = hipErrorInvalidSymbol;
+      if (err == hipSuccess) g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+  }
+  if (err != hipSuccess) {
+    g_last_hip_error = (int)err;
+    return SPAN_ERR_HIP;
+  }
+  return SPAN_OK;
+}
+
 template <class Elt, int D, bool kDense, int NQ>
 int launch_typed(const LaunchArgsTable& a, bool use_table, int batch, hipStream_t stream) {
   // K loads (and as many V loads) a wave has in flight before it consumes the first: 4 KiB + 4 KiB, but
@@ -816,6 +849,37 @@ extern "C" int span_decode_attn(const span_attn_desc_t* desc, const void* q, con
                                 const int32_t* span_ends, const int32_t* ctx_lens, float scale, float* out) {
   (void)ctx_lens;
   return spanattn::launch<false>(desc, q, k_cache, v_cache, span_offsets, span_starts, span_ends, nullptr, scale, out);
+}
+
+extern "C" int span_decode_attn_static(const span_attn_desc_t* desc, const void* q, const void* k_cache,
+                                       const void* v_cache, const int32_t* span_offsets, const int32_t* span_starts,
+                                       const int32_t* span_ends, const int32_t* ctx_lens, float scale, float* out) {
+  (void)ctx_lens;
+  const int rc = spanattn::check_desc(desc);
+  if (rc != SPAN_OK) return rc;
+  span_attn_desc_t d = *desc;
+  d.workspace = nullptr;
+  d.workspace_bytes = 0;
+  const spanattn::Partition p = spanattn::plan_partition(&d);
+  const size_t need = spanattn::workspace_bytes(&d, p);
+  if (need > SPAN_STATIC_SCRATCH_BYTES) return SPAN_ERR_SCRATCH_LIMIT;
+  if (need > 0) {
+    void* ptr = nullptr;
+    const int src = spanattn::static_scratch(&ptr);
+    if (src != SPAN_OK) return src;
+    d.workspace = ptr;
+    d.workspace_bytes = SPAN_STATIC_SCRATCH_BYTES;
+    // the array keeps what the last call (of any shape) left: the tickets of this call's pairs start at zero
+    const size_t words = spanattn::workspace_counter_bytes(&d) / sizeof(uint32_t);
+    hipLaunchKernelGGL(spanattn::zero_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)d.stream, (uint32_t*)ptr, words);
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+      spanattn::g_last_hip_error = (int)err;
+      return SPAN_ERR_HIP;
+    }
+  }
+  return spanattn::launch<false>(&d, q, k_cache, v_cache, span_offsets, span_starts, span_ends, nullptr, scale, out);
 }
 
 extern "C" int span_decode_attn_multi(const span_attn_desc_t* desc, const void* q, const void* k_cache,

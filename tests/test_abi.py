@@ -28,18 +28,18 @@ def test_library_exports_every_declared_symbol():
     assert {"span_decode_attn", "dense_decode_attn", "span_validate", "span_plan_query", "span_workspace_bytes",
             "span_workspace_init", "span_strerror", "span_last_hip_error", "span_blocks_to_intervals",
             "span_intervals_to_blocks", "span_build", "span_decode_attn_append", "dense_decode_attn_append",
-            "span_decode_attn_multi", "span_advance"} <= set(names)
+            "span_decode_attn_multi", "span_advance", "span_decode_attn_static"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
 
 def test_strerror_covers_all_codes():
     seen = set()
-    for code in range(-6, 7):
+    for code in range(-7, 7):
         s = span.span_strerror(code)
         assert s and s != "unknown code"
         seen.add(s)
-    assert len(seen) == 13
+    assert len(seen) == 14
     assert span.span_strerror(99) == "unknown code"
 
 

@@ -85,6 +85,21 @@ typedef struct span_attn_desc {
   void* stream;            /* hipStream_t; NULL = the default stream                             */
   int32_t q_len;           /* query tokens per sequence: 0 or 1 for every entry point but
                               span_decode_attn_multi, which takes 1..64                          */
+  const int32_t* host_span_offsets; /* HOST copies of span_offsets / span_starts / span_ends (the arrays     */
+  const int32_t* host_span_starts;  /* span_validate was given), or all NULL.  The span is chosen once per   */
+  const int32_t* host_span_ends;    /* group of tokens (Sec. 3.2 "Overhead"), so the host has the lists at
+                              hand.  With them the library counts the attended positions itself
+                              (tokens_per_seq is not consulted) and, when the sequences are cut into
+                              different numbers of slices and the batch is small enough (<= 96 slices
+                              and <= 288 position runs in all, <= 1024 positions per slice), resolves
+                              every slice to its runs of cache positions on the host and passes the
+                              runs in the kernel arguments in place of the slice table: the kernel
+                              then reads no span metadata from device memory (about 2 % faster on
+                              raggedly sliced batches).  The result is the same, bit for bit.  They must
+                              describe the same spans as the device arrays (not checked; memory safety
+                              does not depend on it) and are read during the call only.  Leave them
+                              NULL when the device lists change without the host knowing (span_advance
+                              inside a replayed graph) and for the dense calls.                        */
 } span_attn_desc_t;
 
 /*
@@ -224,6 +239,8 @@ typedef struct span_plan_info {
   int32_t slice_limit;     /* most positions one slice can own (a constant of the build)                */
   int64_t workgroups;      /* workgroups the call launches                                        */
   int64_t workspace_bytes; /* same value as span_workspace_bytes()                                */
+  int32_t runs_in_arguments; /* 1: host_span_* were given and the plan fits: the slices' position runs
+                              travel in the kernel arguments (span form)                          */
 } span_plan_info_t;
 int span_plan_query(const span_attn_desc_t* desc, span_plan_info_t* info);
 

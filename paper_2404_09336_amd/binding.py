@@ -26,30 +26,37 @@ class _Desc(ctypes.Structure):
                 ("max_len", ctypes.c_int32), ("dtype", ctypes.c_int32), ("num_intervals", ctypes.c_int32),
                 ("max_tokens", ctypes.c_int32), ("num_splits", ctypes.c_int32),
                 ("tokens_per_seq", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-                ("stream", ctypes.c_void_p), ("q_len", ctypes.c_int32)]
+                ("stream", ctypes.c_void_p), ("q_len", ctypes.c_int32),
+                ("host_span_offsets", ctypes.c_void_p), ("host_span_starts", ctypes.c_void_p),
+                ("host_span_ends", ctypes.c_void_p)]
 
 
 class PlanInfo(ctypes.Structure):
     _fields_ = [("exact", ctypes.c_int32), ("slice_tokens", ctypes.c_int32), ("max_splits", ctypes.c_int32),
-                ("slice_limit", ctypes.c_int32), ("workgroups", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
+                ("slice_limit", ctypes.c_int32), ("workgroups", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64),
+                ("runs_in_arguments", ctypes.c_int32)]
 
     def as_dict(self):
         return {"exact": bool(self.exact), "slice_tokens": self.slice_tokens, "max_splits": self.max_splits,
-                "slice_limit": self.slice_limit, "workgroups": self.workgroups, "workspace_bytes": self.workspace_bytes}
+                "slice_limit": self.slice_limit, "workgroups": self.workgroups, "workspace_bytes": self.workspace_bytes,
+                "runs_in_arguments": bool(self.runs_in_arguments)}
 
 
 def lib_path() -> str:
-    return _LIB_PATH
+    """The product library, or the measurement variant of it that SPAN_ATTN_VARIANT names (see build.py)."""
+    variant = os.environ.get("SPAN_ATTN_VARIANT", "")
+    return os.path.join(_HERE, f"libspanattn_{variant}.so") if variant else _LIB_PATH
 
 
 def load_library():
     """Loads libspanattn.so; raises if it has not been built (no fallback path exists)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB_PATH):
-            raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with "
                                "`python -m paper_2404_09336_amd.build` (needs hipcc)")
-        lib = ctypes.CDLL(_LIB_PATH)
+        lib = ctypes.CDLL(path)
         P, I32, F = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
         DP = ctypes.POINTER(_Desc)
         lib.span_decode_attn.argtypes = [DP, P, P, P, P, P, P, P, F, P]
@@ -100,10 +107,19 @@ def _dtype_code(t):
 
 
 def make_desc(batch, heads, head_dim, max_len, dtype_code, num_intervals=0, max_tokens=0, num_splits=0,
-              workspace_ptr=0, workspace_bytes=0, stream=0, tokens_per_seq=None, q_len=0) -> _Desc:
-    """tokens_per_seq: host int64 numpy array [batch] or None; the descriptor keeps a reference to it."""
+              workspace_ptr=0, workspace_bytes=0, stream=0, tokens_per_seq=None, q_len=0, host_spans=None) -> _Desc:
+    """tokens_per_seq: host int64 numpy array [batch] or None.  host_spans: (offsets, starts, ends) host int32
+    arrays, copies of the device span lists, or None.  The descriptor keeps references to the host arrays."""
     d = _Desc(batch, heads, head_dim, max_len, dtype_code, num_intervals, max_tokens, num_splits, None,
-              workspace_ptr or None, workspace_bytes, stream or None, int(q_len))
+              workspace_ptr or None, workspace_bytes, stream or None, int(q_len), None, None, None)
+    if host_spans is not None:
+        off, st, en = (np.ascontiguousarray(a, dtype=np.int32).reshape(-1) for a in host_spans)
+        if off.shape[0] != batch + 1 or st.shape[0] != num_intervals or en.shape[0] != num_intervals:
+            raise ValueError("host_spans must be (offsets[batch+1], starts[num_intervals], ends[num_intervals])")
+        if st.shape[0] == 0:                       # keep the pointers non-NULL for an empty list
+            st, en = np.zeros(1, np.int32), np.zeros(1, np.int32)
+        d._host_spans_keepalive = (off, st, en)
+        d.host_span_offsets, d.host_span_starts, d.host_span_ends = off.ctypes.data, st.ctypes.data, en.ctypes.data
     if tokens_per_seq is not None:
         tok = np.ascontiguousarray(tokens_per_seq, dtype=np.int64).reshape(-1)
         if tok.shape[0] != batch:
@@ -274,7 +290,7 @@ def _i32_dev(t, n, name):
 
 
 def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, workspace, stream, tokens_per_seq,
-             multi=False):
+             multi=False, host_spans=None):
     import torch
     B, H, L, D = _check_qkv(q, k_cache, v_cache, multi)
     if out is None:
@@ -284,7 +300,7 @@ def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, wo
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
     desc = make_desc(B, H, D, L, _dtype_code(q), num_intervals, int(max_tokens), int(num_splits), 0, 0, stream,
-                     tokens_per_seq, q_len=q.shape[1] if multi else 0)
+                     tokens_per_seq, q_len=q.shape[1] if multi else 0, host_spans=host_spans)
     need = span_workspace_bytes(desc)
     if need:
         fresh = workspace is None
@@ -299,12 +315,12 @@ def _prepare(q, k_cache, v_cache, out, num_intervals, max_tokens, num_splits, wo
 
 def prepare_span_decode_attn_multi(q, k_cache, v_cache, span_offsets, span_starts, span_ends, q_pos, scale,
                                    out=None, *, max_tokens=0, num_splits=0, workspace=None, stream=None,
-                                   tokens_per_seq=None) -> "PreparedCall":
+                                   tokens_per_seq=None, host_spans=None) -> "PreparedCall":
     """Few-query variant: q [B,Q,H,D], q_pos int32 GPU tensor [B] or None, out fp32 [B,Q,H,D]."""
     lib = load_library()
     n_int = int(span_starts.numel())
     desc, out, workspace = _prepare(q, k_cache, v_cache, out, n_int, max_tokens, num_splits, workspace, stream,
-                                    tokens_per_seq, multi=True)
+                                    tokens_per_seq, multi=True, host_spans=host_spans)
     off_p = _i32_dev(span_offsets, desc.batch + 1, "span_offsets")
     st_p = _i32_dev(span_starts, n_int, "span_starts")
     en_p = _i32_dev(span_ends, n_int, "span_ends")
@@ -337,11 +353,12 @@ class PreparedCall:
 
 def prepare_span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out=None, *,
                              max_tokens=0, num_splits=0, workspace=None, stream=None,
-                             tokens_per_seq=None) -> PreparedCall:
+                             tokens_per_seq=None, host_spans=None) -> PreparedCall:
+    """host_spans: optional (offsets, starts, ends) host copies of the device span lists (see span_attn.h)."""
     lib = load_library()
     n_int = int(span_starts.numel())
     desc, out, workspace = _prepare(q, k_cache, v_cache, out, n_int, max_tokens, num_splits, workspace, stream,
-                                    tokens_per_seq)
+                                    tokens_per_seq, host_spans=host_spans)
     off_p = _i32_dev(span_offsets, desc.batch + 1, "span_offsets")
     st_p = _i32_dev(span_starts, n_int, "span_starts")
     en_p = _i32_dev(span_ends, n_int, "span_ends")
@@ -356,7 +373,8 @@ STATIC_SCRATCH_BYTES = 4 << 20
 
 
 def prepare_span_decode_attn_static(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out, *,
-                                    max_tokens=0, num_splits=0, stream=None, tokens_per_seq=None) -> PreparedCall:
+                                    max_tokens=0, num_splits=0, stream=None, tokens_per_seq=None,
+                                    host_spans=None) -> PreparedCall:
     """span_decode_attn on the library's own scratch array: no workspace is created or passed, `out` is the
     caller's.  Invoking the prepared call allocates nothing."""
     import torch
@@ -367,7 +385,8 @@ def prepare_span_decode_attn_static(q, k_cache, v_cache, span_offsets, span_star
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
     n_int = int(span_starts.numel())
-    desc = make_desc(B, H, D, L, _dtype_code(q), n_int, int(max_tokens), int(num_splits), 0, 0, stream, tokens_per_seq)
+    desc = make_desc(B, H, D, L, _dtype_code(q), n_int, int(max_tokens), int(num_splits), 0, 0, stream, tokens_per_seq,
+                     host_spans=host_spans)
     ctx_p = _i32_dev(ctx_lens, B, "ctx_lens") if ctx_lens is not None else None
     args = (ctypes.byref(desc), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(),
             _i32_dev(span_offsets, B + 1, "span_offsets"), _i32_dev(span_starts, n_int, "span_starts"),
@@ -401,11 +420,11 @@ def _check_new_rows(q, k_new, v_new):
 
 def prepare_span_decode_attn_append(q, k_new, v_new, k_cache, v_cache, append_pos, span_offsets, span_starts,
                                     span_ends, scale, out=None, *, max_tokens=0, num_splits=0, workspace=None,
-                                    stream=None, tokens_per_seq=None) -> PreparedCall:
+                                    stream=None, tokens_per_seq=None, host_spans=None) -> PreparedCall:
     lib = load_library()
     n_int = int(span_starts.numel())
     desc, out, workspace = _prepare(q, k_cache, v_cache, out, n_int, max_tokens, num_splits, workspace, stream,
-                                    tokens_per_seq)
+                                    tokens_per_seq, host_spans=host_spans)
     _check_new_rows(q, k_new, v_new)
     args = (ctypes.byref(desc), q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), k_cache.data_ptr(),
             v_cache.data_ptr(), _i32_dev(append_pos, desc.batch, "append_pos"),
@@ -442,11 +461,11 @@ def dense_decode_attn_append(q, k_new, v_new, k_cache, v_cache, append_pos, ctx_
 
 
 def span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out=None, *,
-                     max_tokens=0, num_splits=0, workspace=None, stream=None, tokens_per_seq=None):
+                     max_tokens=0, num_splits=0, workspace=None, stream=None, tokens_per_seq=None, host_spans=None):
     """out[b,h,:] = softmax over the span's positions of scale*q.K, times V.  Returns `out` (fp32)."""
     return prepare_span_decode_attn(q, k_cache, v_cache, span_offsets, span_starts, span_ends, ctx_lens, scale, out,
                                     max_tokens=max_tokens, num_splits=num_splits, workspace=workspace,
-                                    stream=stream, tokens_per_seq=tokens_per_seq)()
+                                    stream=stream, tokens_per_seq=tokens_per_seq, host_spans=host_spans)()
 
 
 def dense_decode_attn(q, k_cache, v_cache, ctx_lens, scale, out=None, *, max_tokens=0, num_splits=0,

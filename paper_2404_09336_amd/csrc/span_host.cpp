@@ -87,10 +87,11 @@ static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // equal-sized.  When batch * heads alone exceeds a round, every sequence is one slice.
 static int64_t slices_for(int64_t n, int64_t T) { return n <= 0 ? 1 : ceil_div(n, T); }
 
-static bool plan_exact(const span_attn_desc_t* d, int64_t max_tok, Partition* p, uint32_t* table) {
-  if (!d->tokens_per_seq || d->num_splits != 0 || d->batch > kMaxPlanBatch) return false;
+static bool plan_exact(const span_attn_desc_t* d, const int64_t* tokens_per_seq, int64_t max_tok, Partition* p,
+                       uint32_t* table) {
+  if (!tokens_per_seq || d->num_splits != 0 || d->batch > kMaxPlanBatch) return false;
   auto tokens = [&](int32_t b) {
-    const int64_t n = d->tokens_per_seq[b];
+    const int64_t n = tokens_per_seq[b];
     return n < 0 ? (int64_t)0 : (n > max_tok ? max_tok : n);
   };
   auto count = [&](int64_t T) {
@@ -175,16 +176,98 @@ static bool plan_exact(const span_attn_desc_t* d, int64_t max_tok, Partition* p,
   p->max_tokens = (int32_t)max_tok;
   p->total_slices = (int32_t)total;
   p->queries_per_pass = queries_per_pass(d);
+  p->granule = (int32_t)T;
+  p->runs = false;
   return true;
+}
+
+static bool has_host_lists(const span_attn_desc_t* d) {
+  return d->host_span_offsets && (d->num_intervals == 0 || (d->host_span_starts && d->host_span_ends));
+}
+
+// Attended positions of every sequence from the host copies of the span lists, with the clamps the kernel applies
+// to the device lists (interval indices to [0, num_intervals], lengths to [0, max_len]).
+static void tokens_from_host_lists(const span_attn_desc_t* d, std::vector<int64_t>* tokens) {
+  tokens->assign((size_t)d->batch, 0);
+  for (int32_t b = 0; b < d->batch; ++b) {
+    const int32_t lo = std::min(std::max(d->host_span_offsets[b], 0), d->num_intervals);
+    const int32_t hi = std::min(std::max(d->host_span_offsets[b + 1], lo), d->num_intervals);
+    int64_t n = 0;
+    for (int32_t i = lo; i < hi; ++i)
+      n += std::min<int64_t>(std::max<int64_t>((int64_t)d->host_span_ends[i] - d->host_span_starts[i], 0), d->max_len);
+    (*tokens)[(size_t)b] = n;
+  }
+}
+
+// Run mode: resolves each slice of an exact plan to its runs of consecutive cache positions.  Sequence b has
+// n_b attended positions, numbered 0 .. n_b-1 along its interval list, and ceil(n_b / granule) slices that share
+// them evenly (as the kernel cuts them when it walks the device lists itself).  False if the plan does not fit the
+// tables or a slice is larger than one position window per wave allows.
+static bool plan_runs(const span_attn_desc_t* d, const int64_t* tokens_per_seq, const Partition& p, RunTables* r) {
+  if (!p.even || d->batch > kMaxPlanBatch || p.total_slices > kMaxRunSlices) return false;
+  int32_t y = 0, nruns = 0;
+  for (int32_t b = 0; b < d->batch; ++b) {
+    int64_t n = tokens_per_seq[b] < 0 ? 0 : tokens_per_seq[b];
+    if (n > p.max_tokens) n = p.max_tokens;
+    const int64_t nsl = slices_for(n, p.granule), T = ceil_div(n, nsl);
+    if (T > kMaxRunSliceRows || nsl > kMaxPlanSplits) return false;
+    const int32_t lo = std::min(std::max(d->host_span_offsets[b], 0), d->num_intervals);
+    const int32_t hi = std::min(std::max(d->host_span_offsets[b + 1], lo), d->num_intervals);
+    int32_t i = lo;        // interval the walk stands in
+    int64_t before = 0;    // attended positions of the intervals before it
+    for (int64_t s = 0; s < nsl; ++s) {
+      if (y >= kMaxRunSlices) return false;
+      const int64_t v0 = s * T, v1 = std::min(n, (s + 1) * T);  // the slice owns positions number v0 .. v1-1
+      const int32_t first_run = nruns;
+      for (int64_t v = v0; v < v1;) {
+        int64_t len = 0;
+        while (i < hi) {  // skip to the interval that holds position number v
+          len = std::min<int64_t>(std::max<int64_t>((int64_t)d->host_span_ends[i] - d->host_span_starts[i], 0), d->max_len);
+          if (v < before + len) break;
+          before += len;
+          ++i;
+        }
+        if (i >= hi) return false;  // (cannot happen: n was summed over the same list)
+        const int64_t take = std::min(v1, before + len) - v;
+        if (nruns >= kMaxRuns) return false;
+        r->run[nruns][0] = (int32_t)std::min<int64_t>(std::max<int64_t>((int64_t)d->host_span_starts[i] + (v - before), INT32_MIN), INT32_MAX);
+        r->run[nruns][1] = (int32_t)take;
+        ++nruns;
+        v += take;
+      }
+      r->slices[y].entry = pack_slice((uint32_t)b, (uint32_t)s, (uint32_t)nsl);
+      r->slices[y].runs_of = (uint32_t)first_run | ((uint32_t)(nruns - first_run) << 16);
+      r->slices[y].rows = (int32_t)(v1 > v0 ? v1 - v0 : 0);
+      r->slices[y].reserved = 0;
+      ++y;
+    }
+  }
+  return y == p.total_slices;
 }
 
 // Uniform mode: every sequence gets the same number of slices, sized so that a call puts about
 // kTargetWorkgroups workgroups on the chip (256 CUs x 8 resident workgroups), never fewer than kMinSlice
 // positions per slice, never more than the kMaxSlice the kernel's position table holds.
-Partition plan_partition(const span_attn_desc_t* d, uint32_t* table) {
+Partition plan_partition(const span_attn_desc_t* d, uint32_t* table, RunTables* runs) {
   const int64_t max_tok = (d->max_tokens > 0 && d->max_tokens < d->max_len) ? d->max_tokens : d->max_len;
   Partition p;
-  if (plan_exact(d, max_tok, &p, table)) return p;
+  // Host copies of the span lists, when given, are the authority on the token counts (tokens_per_seq is then not
+  // consulted), in every function that plans from this descriptor, so that they all agree.
+  const int64_t* tokens = d->tokens_per_seq;
+  std::vector<int64_t> from_lists;
+  const bool lists = has_host_lists(d) && d->batch <= kMaxPlanBatch;
+  if (lists) {
+    tokens_from_host_lists(d, &from_lists);
+    tokens = from_lists.data();
+  }
+  if (plan_exact(d, tokens, max_tok, &p, table)) {
+    // Run mode pays where the launch carries a slice table anyway (sequences with different numbers of slices):
+    // kernel arguments of that size cost a few tenths of a microsecond per launch, which a batch that needs no
+    // table would pay on top (measured: batch 64 x 155 positions, one slice each, 27.7 -> 27.9 us with runs;
+    // batch 8 and batch 16 sliced raggedly, 24.1 -> 23.7 us and 31.1 -> 30.8 us).
+    if (lists && runs && p.exact) p.runs = plan_runs(d, tokens, p, runs);
+    return p;
+  }
   const int64_t pairs = (int64_t)d->batch * d->heads;
   int64_t splits = d->num_splits > 0 ? d->num_splits : target_workgroups(d) / pairs;  // stay within one round
   const int64_t most = ceil_div(max_tok, kMinSlice);
@@ -202,6 +285,8 @@ Partition plan_partition(const span_attn_desc_t* d, uint32_t* table) {
   p.max_tokens = (int32_t)max_tok;
   p.total_slices = (int32_t)(splits * d->batch);
   p.queries_per_pass = queries_per_pass(d);
+  p.granule = (int32_t)slice;
+  p.runs = false;
   return p;
 }
 
@@ -227,7 +312,9 @@ extern "C" int span_plan_query(const span_attn_desc_t* desc, span_plan_info_t* i
   if (!info) return SPAN_ERR_NULL;
   const int rc = spanattn::check_desc(desc);
   if (rc != SPAN_OK) return rc;
-  const spanattn::Partition p = spanattn::plan_partition(desc);
+  spanattn::RunTables runs;
+  const spanattn::Partition p = spanattn::plan_partition(desc, nullptr, &runs);
+  info->runs_in_arguments = p.runs ? 1 : 0;
   info->exact = p.even ? 1 : 0;
   info->slice_tokens = p.slice_tokens;
   info->max_splits = p.num_splits;

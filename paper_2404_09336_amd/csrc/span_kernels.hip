@@ -74,17 +74,75 @@ struct LaunchArgs {
   int32_t total_slices;             // table mode: entries of `table` in use
   int32_t even;                     // 1: a sequence's slices share its own token count evenly; 0: slice_tokens each
   int32_t interleave;               // 1: rows dealt to the waves round-robin (large slices); 0: contiguous quarters
+#ifdef SPAN_PHASE_TRACE
+  unsigned long long* trace;        // diagnostic build only: [trace_workgroups, kTraceStamps] times of the phases, or null
+  size_t trace_workgroups;
+#endif
 };
 // Table mode: blockIdx.y indexes `table` (sequences have different numbers of slices).  The table makes
 // the kernel arguments 3 KB larger, which costs about 0.35 us per launch, so calls that do not need it
 // (every sequence has the same number of slices) use the plain arguments and a (heads, slices, batch) grid.
 struct LaunchArgsTable : LaunchArgs {
   static constexpr bool kHasTable = true;
+  static constexpr bool kHasRuns = false;
   uint32_t table[kMaxPlanSlices];   // pack_slice(batch, slice, slices of the sequence)
 };
 struct LaunchArgsPlain : LaunchArgs {
   static constexpr bool kHasTable = false;
+  static constexpr bool kHasRuns = false;
 };
+// Run mode: blockIdx.y indexes the slices of all sequences, each resolved on the host to its runs of consecutive
+// cache positions; the kernel reads no span metadata from device memory.
+struct LaunchArgsRuns : LaunchArgs {
+  static constexpr bool kHasTable = true;
+  static constexpr bool kHasRuns = true;
+  RunTables r;
+};
+
+// Diagnostic build (-DSPAN_PHASE_TRACE): every workgroup reads the constant-rate (100 MHz) clock at the phase
+// boundaries named below into registers and thread 0 writes them out when the workgroup ends, so that taking a stamp
+// puts no memory operation into the path it measures.  Each stamp names a value that must have been computed before
+// the clock is read (the compiler may not move the read ahead of it).  The regular build compiles the stamps away.
+// stamps: 0 kernel entry, 10 the sequence's interval range read (device lists), 1 span metadata read and slice known,
+// 2 first position table built, 3 first K / V rows consumed, 4 all rows consumed, 5 waves merged in LDS, 6 output row
+// stored and acknowledged (one slice per pair), 7 partial state published and acknowledged, 8 ticket returned,
+// 9 slices merged, output row stored and acknowledged (last arrival only)
+constexpr int kTraceStamps = 16;
+#ifdef SPAN_PHASE_TRACE
+#define SPAN_TRACE_DECL unsigned long long trace_t[11] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}
+#define SPAN_STAMP_AFTER(i, constraint, value)        \
+  do {                                                \
+    asm volatile("" ::constraint(value) : "memory");  \
+    trace_t[i] = wall_clock64();                      \
+    asm volatile("" ::: "memory");                    \
+  } while (0)
+#define SPAN_STAMP_ACKED(i)                                  \
+  do {                                                       \
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); \
+    trace_t[i] = wall_clock64();                             \
+    asm volatile("" ::: "memory");                           \
+  } while (0)
+#define SPAN_TRACE_FLUSH()                                                                                     \
+  do {                                                                                                         \
+    const size_t wg_ = (size_t)(blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;                 \
+    if (threadIdx.x == 0 && a.trace && wg_ < a.trace_workgroups) {                                             \
+      for (int i_ = 0; i_ < 11; ++i_) a.trace[wg_ * kTraceStamps + i_] = trace_t[i_];                          \
+    }                                                                                                          \
+  } while (0)
+#else
+#define SPAN_TRACE_DECL \
+  do {                  \
+  } while (0)
+#define SPAN_STAMP_AFTER(i, constraint, value) \
+  do {                                         \
+  } while (0)
+#define SPAN_STAMP_ACKED(i) \
+  do {                      \
+  } while (0)
+#define SPAN_TRACE_FLUSH() \
+  do {                     \
+  } while (0)
+#endif
 
 // ---- storage types ---------------------------------------------------------------------------------
 // unpack: 16 bytes of a row -> fp32 (for the V accumulation).
@@ -209,7 +267,10 @@ __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? l
 // K / V rows are fetched with raw buffer loads: the descriptor covers exactly one (batch, head) slab,
 // so the hardware itself returns zeros for any offset outside it, and the cache policy is explicit.
 // Non-temporal (streaming) loads: every row is used once; measured 17 % faster than default-policy loads.
-constexpr int kRowLoadPolicy = 2;  // bit 0 = sc0, bit 1 = nt, bit 4 = sc1
+#ifndef SPAN_ROW_LOAD_POLICY
+#define SPAN_ROW_LOAD_POLICY 2  // (a measurement build overrides it to time the other policies)
+#endif
+constexpr int kRowLoadPolicy = SPAN_ROW_LOAD_POLICY;  // bit 0 = sc0, bit 1 = nt, bit 4 = sc1
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const void* slab, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(slab), 0, bytes, 0x00020000);
 }
@@ -231,8 +292,10 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int 
   const float mn = fmaxf(m, m2);
   const float ms = (mn == -INFINITY) ? 0.f : mn;
   const float a = __builtin_amdgcn_exp2f(m - ms), b = __builtin_amdgcn_exp2f(m2 - ms);
-  l = l * a + l2 * b;
-  for (int i = 0; i < n; ++i) acc[i] = acc[i] * a + acc2[i] * b;
+  // one rounding order, written out: the compiler may contract x*a + y*b either way round, and every instance of
+  // the kernel has to give the same bits
+  l = fmaf(l, a, l2 * b);
+  for (int i = 0; i < n; ++i) acc[i] = fmaf(acc[i], a, acc2[i] * b);
   m = mn;
 }
 
@@ -250,10 +313,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
 
   // heads vary fastest: consecutive workgroups go to different XCDs, and the 'is this slice empty'
   // answer is the same for all heads of a (batch, slice), so full and empty slices spread evenly
+  SPAN_TRACE_DECL;
+  SPAN_STAMP_AFTER(0, "s", 0);
   const int h = blockIdx.x;
   int b, split, nsl, y0;  // sequence, slice within it, slices of the sequence, first slice row of the sequence
   if constexpr (Args::kHasTable) {
-    const uint32_t e = a.table[blockIdx.y];
+    uint32_t e;
+    if constexpr (Args::kHasRuns) e = a.r.slices[blockIdx.y].entry;
+    else e = a.table[blockIdx.y];
     b = e & 1023u;
     split = (e >> 10) & 2047u;
     nsl = e >> 21;
@@ -314,13 +381,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   int n_total;
   int n_int = 0, off0 = 0;
   int st0 = 0, len0 = 0, incl0 = 0;  // first chunk of 64 intervals, kept in registers
-  if (kDense) {
+  if constexpr (Args::kHasRuns) {
+    n_total = 0;  // the slice's rows come from the arguments, see below
+  } else if (kDense) {
     n_total = clampi(a.ctx_lens[b], 0, a.max_len);
   } else {
     off0 = clampi(a.offsets[b], 0, a.num_intervals);
     const int off1 = clampi(a.offsets[b + 1], off0, a.num_intervals);
     off0 = __builtin_amdgcn_readfirstlane(off0);
     n_int = __builtin_amdgcn_readfirstlane(off1 - off0);
+    SPAN_STAMP_AFTER(10, "s", n_int);
     if (lane < n_int) {
       st0 = a.starts[off0 + lane];
       len0 = clampi(a.ends[off0 + lane] - st0, 0, a.max_len);
@@ -334,9 +404,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     }
   }
   n_total = n_total < a.max_tokens ? n_total : a.max_tokens;
-  const int T = a.even ? (n_total + nsl - 1) / nsl : a.slice_tokens;
-  const int slice_begin = split * T;
-  const int cnt = __builtin_amdgcn_readfirstlane(clampi(n_total - slice_begin, 0, T));
+  int slice_begin, cnt;
+  if constexpr (Args::kHasRuns) {  // rows are numbered within the slice
+    slice_begin = 0;
+    cnt = clampi(a.r.slices[blockIdx.y].rows, 0, kMaxRunSliceRows);
+  } else {
+    const int T = a.even ? (n_total + nsl - 1) / nsl : a.slice_tokens;
+    slice_begin = split * T;
+    cnt = __builtin_amdgcn_readfirstlane(clampi(n_total - slice_begin, 0, T));
+  }
+  SPAN_STAMP_AFTER(1, "s", cnt);
 
   // State of this slice for output column tid (tid < D), per query token: un-normalised, m in log2 units.
   float M[NQ], L[NQ], o[NQ];
@@ -449,11 +526,53 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
       if (carry >= vend) break;
     }
   };
-  if (!kDense && nrows > 0) tabulate(std::true_type{}, 0, min(kWin, nrows));
+  if constexpr (Args::kHasRuns) {
+    // Run mode: the slice is a short list of runs [start, start + len) in the kernel arguments.  Row number v of
+    // the slice lies in the last run whose rows-before count is <= v; a wave has at most kWin rows (the host
+    // checked the slice size), four per lane, and walks the runs with scalar loads - no LDS search, and no
+    // vector memory access ahead of the first K row.
+    const uint32_t ro = a.r.slices[blockIdx.y].runs_of;
+    const int run0 = min((int)(ro & 0xffffu), kMaxRuns), nrun = min((int)(ro >> 16), kMaxRuns - run0);
+    int v[kWin / 64], p[kWin / 64];
+#pragma unroll
+    for (int k = 0; k < kWin / 64; ++k) {
+      v[k] = vrow(lane + 64 * k);
+      p[k] = 0;
+    }
+    int before = 0;
+    constexpr int kRunBatch = 8;  // runs fetched together: their scalar loads are all in flight before the first is used
+    for (int j0 = 0; j0 < nrun; j0 += kRunBatch) {
+      int st[kRunBatch], ln[kRunBatch];
+#pragma unroll
+      for (int i = 0; i < kRunBatch; ++i) {
+        const int idx = min(run0 + j0 + i, kMaxRuns - 1);
+        st[i] = a.r.run[idx][0];
+        ln[i] = a.r.run[idx][1];
+      }
+#pragma unroll
+      for (int i = 0; i < kRunBatch; ++i) {
+        const bool live = j0 + i < nrun;
+#pragma unroll
+        for (int k = 0; k < kWin / 64; ++k) p[k] = (live && v[k] >= before) ? st[i] + (v[k] - before) : p[k];
+        before += live ? ln[i] : 0;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kWin / 64; ++k)
+      if (lane + 64 * k < nrows) s_pos[wave][lane + 64 * k] = clampi(p[k], 0, a.max_len - 1);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  } else {
+    if (!kDense && nrows > 0) tabulate(std::true_type{}, 0, min(kWin, nrows));
+  }
+  SPAN_STAMP_AFTER(2, "v", lane_off);
 
   for (int w0 = 0; w0 < nrows; w0 += kWin) {
   const int wn = min(kWin, nrows - w0);  // rows w0 .. w0+wn-1 of mine
-  if (!kDense && w0 > 0) tabulate(std::false_type{}, w0, wn);
+  if constexpr (!Args::kHasRuns) {
+    if (!kDense && w0 > 0) tabulate(std::false_type{}, w0, wn);
+  }
 
   if (a.append_pos) {  // is the appended row one of the window's rows?  Then row group 0 takes it in now.
     bool mine = false;
@@ -554,8 +673,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
         for (int i = 0; i < EPL; ++i) acc[j][i] = fmaf(w[j][u], vf[i], acc[j][i]);
       }
     }
+#ifdef SPAN_PHASE_TRACE
+    if (w0 == 0 && base == 0) SPAN_STAMP_AFTER(3, "v", acc[0][0]);
+#endif
   }
   }  // windows
+  SPAN_STAMP_AFTER(4, "v", acc[0][0]);
 
   // ---- step 4: merge row groups (shuffles), then waves (LDS) ------------------------------------
 #pragma unroll
@@ -587,12 +710,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
 #pragma unroll
       for (int w = 0; w < kWavesPerBlock; ++w) {
         const float wgt = s_ml[w][j][1] > 0.f ? __builtin_amdgcn_exp2f(s_ml[w][j][0] - M[j]) : 0.f;
-        L[j] += wgt * s_ml[w][j][1];
-        o[j] += wgt * s_acc[w][j][tid];
+        L[j] = fmaf(wgt, s_ml[w][j][1], L[j]);
+        o[j] = fmaf(wgt, s_acc[w][j][tid], o[j]);
       }
     }
   }
   }  // cnt > 0
+  SPAN_STAMP_AFTER(5, "v", o[0]);
 
   if (nsl == 1) {  // one slice for this (batch, head): this workgroup owns the output row
     if (tid < D) {
@@ -600,6 +724,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
       for (int j = 0; j < NQ; ++j)
         if (j < nq_here) a.out[qrow(j) * D + tid] = L[j] > 0.f ? o[j] / L[j] : 0.f;
     }
+    SPAN_STAMP_ACKED(6);
+    SPAN_TRACE_FLUSH();
     return;
   }
 
@@ -626,9 +752,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my published stores are acknowledged
   }
   __syncthreads();
+  SPAN_STAMP_AFTER(7, "s", 0);
   if (tid == 0) s_ticket = __hip_atomic_fetch_add(&a.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
-  if (s_ticket != nsl - 1) return;
+  SPAN_STAMP_AFTER(8, "v", s_ticket);
+  if (s_ticket != nsl - 1) {
+    SPAN_TRACE_FLUSH();
+    return;
+  }
 
   constexpr int G = kThreads / D;  // column t is merged by G threads, each over every G-th slice
   const int g = tid / D, t = tid % D;
@@ -640,15 +771,31 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     ll[j] = 0.f;
     oo[j] = 0.f;
   }
-#pragma unroll 4
-  for (int s = g; s < nsl; s += G) {
-    const size_t slot = slot0 + (size_t)s * H;
+  // The states are fetched a batch at a time, all loads of a batch in flight together (one trip to memory for up
+  // to kBatch * G slices), and merged in slice order.
+  constexpr int kBatch = NQ == 1 ? 8 : (NQ == 2 ? 4 : 2);
+  for (int s0 = g; s0 < nsl; s0 += G * kBatch) {
+    float ms[kBatch][NQ], ls[kBatch][NQ], as[kBatch][NQ];
 #pragma unroll
-    for (int j = 0; j < NQ; ++j) {
-      const float ms = observe(&a.part_ml[(slot * NQ + j) * 2]), ls = observe(&a.part_ml[(slot * NQ + j) * 2 + 1]);
-      float as = observe(&a.part_acc[(slot * NQ + j) * D + t]);  // slot of an empty slice is never written: select, do not scale
-      as = ls > 0.f ? as : 0.f;
-      merge_state(mm[j], ll[j], &oo[j], 1, ls > 0.f ? ms : -INFINITY, ls > 0.f ? ls : 0.f, &as);
+    for (int k = 0; k < kBatch; ++k) {
+      const size_t slot = slot0 + (size_t)min(s0 + k * G, nsl - 1) * H;  // (past the end: a slot that exists, unused)
+#pragma unroll
+      for (int j = 0; j < NQ; ++j) {
+        ms[k][j] = observe(&a.part_ml[(slot * NQ + j) * 2]);
+        ls[k][j] = observe(&a.part_ml[(slot * NQ + j) * 2 + 1]);
+        as[k][j] = observe(&a.part_acc[(slot * NQ + j) * D + t]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      if (s0 + k * G < nsl) {
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+          const bool full = ls[k][j] > 0.f;  // slot of an empty slice is never written: select, do not scale
+          const float av = full ? as[k][j] : 0.f;
+          merge_state(mm[j], ll[j], &oo[j], 1, full ? ms[k][j] : -INFINITY, full ? ls[k][j] : 0.f, &av);
+        }
+      }
     }
   }
   if (g > 0) {
@@ -675,6 +822,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     // leave the ticket counter ready for the next call (same device-coherent access path as the tickets)
     if (tid == 0) __hip_atomic_store(&a.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  SPAN_STAMP_ACKED(9);
+  SPAN_TRACE_FLUSH();
 }
 
 // Zeroes n 32-bit words (a plain kernel, so that the call can also be recorded into a HIP graph).
@@ -705,6 +854,10 @@ __global__ __launch_bounds__(256) void advance_kernel(int batch, int max_len, in
 }
 
 thread_local int g_last_hip_error = 0;
+#ifdef SPAN_PHASE_TRACE
+unsigned long long* g_trace = nullptr;  // set by span_debug_set_trace
+size_t g_trace_workgroups = 0;
+#endif
 
 // ---- scratch owned by the library, for span_decode_attn_static ---------------------------------------
 // One array per GPU the library runs on, resident until the process ends.  `scratch` is only a host-side
@@ -738,14 +891,31 @@ int static_scratch(void** ptr) {
   return SPAN_OK;
 }
 
+// How the grid names its slices.
+enum class GridMode { kPlain, kTable, kRuns };
+
 template <class Elt, int D, bool kDense, int NQ>
-int launch_typed(const LaunchArgsTable& a, bool use_table, int batch, hipStream_t stream) {
+int launch_typed(const LaunchArgsTable& a, const RunTables* runs, GridMode mode, int batch, hipStream_t stream) {
   // K loads (and as many V loads) a wave has in flight before it consumes the first: 4 KiB + 4 KiB, but
   // never more than 16 rows (with 128-byte rows that is 2 instructions of 8 rows); half of that when
   // several query tokens share the registers
   constexpr int kRowsPerLoad = 64 / (D / Elt::kPerVec);
+#ifdef SPAN_IN_FLIGHT
+  constexpr int kInFlight = SPAN_IN_FLIGHT;
+#else
   constexpr int kInFlight = (kRowsPerLoad >= 8 ? 2 : 4) / (NQ > 1 ? 2 : 1);
-  if (use_table) {
+#endif
+  if (mode == GridMode::kRuns) {
+    if constexpr (!kDense) {
+      const dim3 grid((unsigned)a.heads, (unsigned)a.total_slices, 1u);
+      LaunchArgsRuns ra;
+      static_cast<LaunchArgs&>(ra) = static_cast<const LaunchArgs&>(a);
+      ra.r = *runs;
+      hipLaunchKernelGGL((decode_kernel<Elt, D, false, kInFlight, NQ, LaunchArgsRuns>), grid, dim3(kThreads), 0, stream, ra);
+    } else {
+      return SPAN_ERR_SHAPE;  // (not reachable: the dense form never plans runs)
+    }
+  } else if (mode == GridMode::kTable) {
     const dim3 grid((unsigned)a.heads, (unsigned)a.total_slices, 1u);
     hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsTable>), grid, dim3(kThreads), 0, stream, a);
   } else {
@@ -763,12 +933,13 @@ int launch_typed(const LaunchArgsTable& a, bool use_table, int batch, hipStream_
 }
 
 template <class Elt, int D, bool kDense>
-int launch_queries(const LaunchArgsTable& a, int nq, bool use_table, int batch, hipStream_t stream) {
+int launch_queries(const LaunchArgsTable& a, const RunTables* runs, int nq, GridMode mode, int batch,
+                   hipStream_t stream) {
   if constexpr (!kDense) {  // the few-query variant exists for the span form only
-    if (nq == 2) return launch_typed<Elt, D, false, 2>(a, use_table, batch, stream);
-    if (nq == 4) return launch_typed<Elt, D, false, 4>(a, use_table, batch, stream);
+    if (nq == 2) return launch_typed<Elt, D, false, 2>(a, runs, mode, batch, stream);
+    if (nq == 4) return launch_typed<Elt, D, false, 4>(a, runs, mode, batch, stream);
   }
-  return launch_typed<Elt, D, kDense, 1>(a, use_table, batch, stream);
+  return launch_typed<Elt, D, kDense, 1>(a, runs, mode, batch, stream);
 }
 
 template <bool kDense>
@@ -782,7 +953,15 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   if (!q || !k || !v || !out) return SPAN_ERR_NULL;
   if (kDense ? !ctx_lens : (!offsets || (d->num_intervals > 0 && (!starts || !ends)))) return SPAN_ERR_NULL;
   LaunchArgsTable a;
-  const Partition p = plan_partition(d, a.table);
+  RunTables runs;
+  span_attn_desc_t own;
+  if (kDense && (d->host_span_offsets || d->host_span_starts || d->host_span_ends)) {
+    own = *d;  // span lists mean nothing to the dense form
+    own.host_span_offsets = own.host_span_starts = own.host_span_ends = nullptr;
+    d = &own;
+  }
+  const Partition p = plan_partition(d, a.table, kDense ? nullptr : &runs);
+  const GridMode mode = p.runs ? GridMode::kRuns : (p.exact ? GridMode::kTable : GridMode::kPlain);
   const size_t need = workspace_bytes(d, p);
   if (need > 0 && (!d->workspace || ((uintptr_t)d->workspace & 255u) || d->workspace_bytes < need))
     return SPAN_ERR_WORKSPACE;
@@ -813,6 +992,10 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
   a.interleave = p.slice_tokens >= kInterleaveFrom ? 1 : 0;
   a.total_slices = p.total_slices;
   a.scale_log2e = scale * 1.4426950408889634f;
+#ifdef SPAN_PHASE_TRACE
+  a.trace = g_trace;
+  a.trace_workgroups = g_trace_workgroups;
+#endif
   hipStream_t stream = (hipStream_t)d->stream;
 
   // One pass over the span serves up to p.queries_per_pass query tokens; more tokens take more passes,
@@ -824,16 +1007,16 @@ int launch(const span_attn_desc_t* d, const void* q, const void* k, const void* 
     int lrc;
     switch (d->dtype) {
       case SPAN_F32:
-        lrc = d128 ? launch_queries<F32, 128, kDense>(a, nq, p.exact, d->batch, stream)
-                   : launch_queries<F32, 64, kDense>(a, nq, p.exact, d->batch, stream);
+        lrc = d128 ? launch_queries<F32, 128, kDense>(a, &runs, nq, mode, d->batch, stream)
+                   : launch_queries<F32, 64, kDense>(a, &runs, nq, mode, d->batch, stream);
         break;
       case SPAN_F16:
-        lrc = d128 ? launch_queries<F16, 128, kDense>(a, nq, p.exact, d->batch, stream)
-                   : launch_queries<F16, 64, kDense>(a, nq, p.exact, d->batch, stream);
+        lrc = d128 ? launch_queries<F16, 128, kDense>(a, &runs, nq, mode, d->batch, stream)
+                   : launch_queries<F16, 64, kDense>(a, &runs, nq, mode, d->batch, stream);
         break;
       default:
-        lrc = d128 ? launch_queries<BF16, 128, kDense>(a, nq, p.exact, d->batch, stream)
-                   : launch_queries<BF16, 64, kDense>(a, nq, p.exact, d->batch, stream);
+        lrc = d128 ? launch_queries<BF16, 128, kDense>(a, &runs, nq, mode, d->batch, stream)
+                   : launch_queries<BF16, 64, kDense>(a, &runs, nq, mode, d->batch, stream);
         break;
     }
     if (lrc != SPAN_OK) return lrc;
@@ -946,3 +1129,12 @@ extern "C" int span_workspace_init(const span_attn_desc_t* desc) {
 }
 
 extern "C" int span_last_hip_error(void) { return spanattn::g_last_hip_error; }
+
+#ifdef SPAN_PHASE_TRACE
+// Diagnostic build only: device buffer of workgroups * 16 64-bit words that every later launch stamps (null = off);
+// workgroups of a launch beyond `workgroups` leave no stamp.
+extern "C" void span_debug_set_trace(void* device_words, size_t workgroups) {
+  spanattn::g_trace = (unsigned long long*)device_words;
+  spanattn::g_trace_workgroups = device_words ? workgroups : 0;
+}
+#endif

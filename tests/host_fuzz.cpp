@@ -3,6 +3,7 @@
 // every array is heap-allocated at exactly the documented size, so any out-of-bounds access, signed overflow
 // or use of an uninitialised slot the sanitizers can see aborts the run.  Results are also cross-checked
 // against brute force where that is cheap.
+#include <algorithm>
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
@@ -203,7 +204,95 @@ static void fuzz_plan() {
   }
 }
 
+// Run mode: with host copies of the span lists the planner resolves every slice to runs of cache positions.
+// Brute force: write out the attended positions of each sequence in list order (with the clamps the kernel
+// applies), cut them into the sequence's slices, and compare with what the runs enumerate.  Lists are mostly
+// valid, sometimes garbage (negative lengths, offsets out of order or out of range).
+static void fuzz_runs() {
+  std::vector<uint32_t> table(spanattn::kMaxPlanSlices);
+  int used = 0;
+  for (int it = 0; it < 6000; ++it) {
+    span_attn_desc_t d = {};
+    d.batch = rnd(1, rnd(0, 3) ? 12 : 70);
+    d.heads = rnd(0, 2) ? 32 : rnd(1, 64);
+    d.head_dim = 128;
+    d.max_len = rnd(0, 3) ? rnd(64, 5000) : rnd(1, 40);
+    d.dtype = 1;
+    d.q_len = rnd(0, 3) ? 0 : rnd(1, 8);
+    const bool garbage = rnd(0, 9) == 0;
+    std::vector<int32_t> off(d.batch + 1, 0), st, en;
+    for (int b = 0; b < d.batch; ++b) {
+      const int k = rnd(0, rnd(0, 4) ? 6 : 40);
+      int pos = 0;
+      for (int i = 0; i < k; ++i) {
+        const int gap = rnd(0, 30), len = rnd(1, rnd(0, 2) ? 40 : 700);
+        int s0 = pos + gap, e0 = s0 + len;
+        if (e0 > d.max_len && !garbage) break;
+        if (garbage && rnd(0, 5) == 0) e0 = s0 - rnd(0, 5);
+        st.push_back(s0);
+        en.push_back(e0);
+        pos = e0 > pos ? e0 : pos;
+      }
+      off[b + 1] = (int32_t)st.size();
+      if (garbage && rnd(0, 6) == 0) off[b + 1] = rnd(-3, (int)st.size() + 3);
+    }
+    d.num_intervals = (int32_t)st.size();
+    if (garbage && d.num_intervals > 0 && rnd(0, 3) == 0) d.num_intervals -= 1;  // lists longer than declared
+    d.max_tokens = rnd(0, 3) ? 0 : rnd(1, d.max_len);
+    d.host_span_offsets = off.data();
+    d.host_span_starts = st.data();  // exactly as long as the list: any read past num_intervals is caught
+    d.host_span_ends = en.data();
+    std::vector<int64_t> wrong(d.batch, 1);
+    d.tokens_per_seq = rnd(0, 1) ? wrong.data() : nullptr;  // not consulted when the lists are there
+    std::vector<spanattn::RunTables> rt(1);                   // heap copy: reads past the tables are caught too
+    const spanattn::Partition p = spanattn::plan_partition(&d, table.data(), rt.data());
+    span_plan_info_t info;
+    REQUIRE(span_plan_query(&d, &info) == SPAN_OK);
+    REQUIRE((info.runs_in_arguments != 0) == p.runs);
+    REQUIRE(info.workspace_bytes == (int64_t)span_workspace_bytes(&d));
+    if (!p.runs) continue;
+    ++used;
+    const spanattn::RunTables& r = rt[0];
+    REQUIRE(p.even && p.total_slices <= spanattn::kMaxRunSlices);
+    const int64_t max_tok = (d.max_tokens > 0 && d.max_tokens < d.max_len) ? d.max_tokens : d.max_len;
+    int y = 0;
+    for (int b = 0; b < d.batch; ++b) {
+      std::vector<int64_t> want;  // attended positions in list order, before the position clamp
+      const int lo = std::min(std::max(off[b], 0), d.num_intervals), hi = std::min(std::max(off[b + 1], lo), d.num_intervals);
+      for (int i = lo; i < hi; ++i) {
+        const int64_t len = std::min<int64_t>(std::max<int64_t>((int64_t)en[i] - st[i], 0), d.max_len);
+        for (int64_t t = 0; t < len; ++t) want.push_back((int64_t)st[i] + t);
+      }
+      if ((int64_t)want.size() > max_tok) want.resize((size_t)max_tok);
+      const int64_t n = (int64_t)want.size();
+      const uint32_t e0 = r.slices[y].entry;
+      const int nsl = (int)(e0 >> 21);
+      REQUIRE(nsl >= 1);
+      const int64_t T = (n + nsl - 1) / nsl;
+      for (int s = 0; s < nsl; ++s, ++y) {
+        REQUIRE(y < p.total_slices);
+        const uint32_t e = r.slices[y].entry;
+        REQUIRE((int)(e & 1023) == b && (int)((e >> 10) & 2047) == s && (int)(e >> 21) == nsl);
+        const int run0 = (int)(r.slices[y].runs_of & 0xffff), nrun = (int)(r.slices[y].runs_of >> 16);
+        REQUIRE(run0 + nrun <= spanattn::kMaxRuns);
+        std::vector<int64_t> got;
+        for (int j = run0; j < run0 + nrun; ++j) {
+          REQUIRE(r.run[j][1] > 0);
+          for (int t = 0; t < r.run[j][1]; ++t) got.push_back((int64_t)r.run[j][0] + t);
+        }
+        const int64_t v0 = std::min<int64_t>(n, (int64_t)s * T), v1 = std::min<int64_t>(n, (int64_t)(s + 1) * T);
+        REQUIRE((int64_t)got.size() == v1 - v0 && r.slices[y].rows == (int32_t)(v1 - v0));
+        REQUIRE(r.slices[y].rows <= spanattn::kMaxRunSliceRows);
+        for (int64_t v = v0; v < v1; ++v) REQUIRE(got[(size_t)(v - v0)] == want[(size_t)v]);
+      }
+    }
+    REQUIRE(y == p.total_slices);
+  }
+  REQUIRE(used > 500);  // the mode was actually exercised
+}
+
 int main() {
+  fuzz_runs();
   fuzz_validate();
   fuzz_build();
   fuzz_blocks();

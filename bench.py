@@ -9,7 +9,8 @@ between two uses of a buffer exceed the on-package cache: the figure is HBM band
 
 Prints ONE JSON line:
   value    = span bytes (K and V rows inside the intervals) * steps / wall time of the timed region  [GB/s];
-             the timed region of exactly `steps` calls is run `rounds` times and the median round is reported
+             the timed region of exactly `steps` calls (synchronize on both sides, nothing else inside) is run
+             `rounds` times and the median round is reported
   roofline = same bytes / average call duration from HIP events on the launch stream, against 8 TB/s
   workloads, coverage_sweep, instances, few_query, unstructured_masks = the other configurations, each with its
              dense control, timed in the same run (compact rows)
@@ -133,17 +134,12 @@ def auto_copies(cfg, touched=None):
     return n
 
 
-def wait_for(event):
-    """Spin on the event instead of sleeping in synchronize(): the host sees the end of the GPU work within about a
-    microsecond, so the wall clock of a short timed region is not inflated by a thread wake-up."""
-    while not event.query():
-        pass
-
-
 def timed_loop(calls, nbytes, steps, warmup, rounds=1):
-    """Warm up, then time exactly `steps` calls, `rounds` times over: wall clock bracketed by synchronize, plus HIP
-    events recorded on the launch stream.  Every round starts at the same rotated copy, so all rounds move the same
-    bytes.  Returns the median round (by wall clock) and the per-round times."""
+    """Warm up, then time exactly `steps` calls, `rounds` times over, two ways: by the wall clock, bracketed by
+    synchronize() on both sides with nothing but the calls in between; and, in a round of its own, by HIP events
+    recorded on the launch stream (the events would add their own cost to the wall-clock region).  Every round starts
+    at the same rotated copy, so all rounds move the same bytes.  Returns the median round of each kind and the
+    per-round times."""
     import torch
     n = len(calls)
     for i in range(warmup):
@@ -151,16 +147,18 @@ def timed_loop(calls, nbytes, steps, warmup, rounds=1):
     total_bytes = sum(nbytes[i % n] for i in range(steps))
     walls, evs = [], []
     for _ in range(max(1, rounds)):
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        for i in range(steps):
+            calls[i % n]()
+        torch.cuda.synchronize()
+        walls.append(time.perf_counter() - t0)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ev0.record()
         for i in range(steps):
             calls[i % n]()
         ev1.record()
-        wait_for(ev1)
         torch.cuda.synchronize()
-        walls.append(time.perf_counter() - t0)
         evs.append(ev0.elapsed_time(ev1) * 1e-3)
     wall, ev_s = statistics.median(walls), statistics.median(evs)
     return {"wall_s": wall, "event_s": ev_s, "bytes_per_call": total_bytes / steps,

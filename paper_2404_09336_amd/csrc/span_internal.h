@@ -17,7 +17,10 @@ constexpr int kMaxSlice = 1 << 22;         // a slice may be a whole sequence (p
 constexpr int kMinSlice = SPAN_MIN_SLICE;  // do not cut work finer than this many positions
 constexpr int kSliceGranule = 16;
 constexpr int kUnsplitFromPairs = 512;     // level batches with at least this many (batch, head) pairs are not sliced
-constexpr int kLargeSlice = 1024;          // slices above this size are cut down to it, in several rounds of workgroups
+#ifndef SPAN_LARGE_SLICE
+#define SPAN_LARGE_SLICE 1024
+#endif
+constexpr int kLargeSlice = SPAN_LARGE_SLICE;  // slices above this size are cut down to it, in several rounds of workgroups
 constexpr int kMaxLen = 1 << 22;           // keeps every in-slab byte offset inside 32 bits
 #ifndef SPAN_TARGET_WORKGROUPS
 #define SPAN_TARGET_WORKGROUPS 2048

@@ -144,19 +144,21 @@ def test_partition_arithmetic_exact():
 
 
 def test_partition_follows_the_query_token_count():
-    """One resident round is 2048 workgroups for one query token, 1536 for two, 1024 for three or more; the
-    workspace grows with the tokens one pass serves (1, 2 or 4), never with q_len itself."""
-    tok = np.full(8, 4096)
+    """One resident round is 2048 workgroups for one query token, 1536 for two, 1024 for three or more, and a
+    ragged batch of 30 sequences (two slices per sequence wanted) is capped by it; the workspace grows with the
+    tokens one pass serves (1, 2 or 4), never with q_len itself."""
+    tok = np.linspace(1500, 4096, 30).astype(np.int64)
     plans = {}
     for q_len in (0, 1, 2, 3, 4, 8, 64):
-        d = binding.make_desc(8, 32, 128, 4096, 1, 10, 4096, 0, tokens_per_seq=tok, q_len=q_len)
+        d = binding.make_desc(30, 32, 128, 4096, 1, 10, 4096, 0, tokens_per_seq=tok, q_len=q_len)
         plans[q_len] = span.span_plan_query(d)
     assert plans[0] == plans[1]
-    assert plans[1]["workgroups"] == 2048 and plans[2]["workgroups"] == 1536 and plans[4]["workgroups"] == 1024
+    assert 1536 < plans[1]["workgroups"] <= 1920           # 2 x 30 slices per head wanted, 64 would fit
+    assert 1024 < plans[2]["workgroups"] <= 1536 and 768 < plans[4]["workgroups"] <= 1024
     assert plans[3] == plans[4] == plans[8] == plans[64]
-    per_slot = lambda pl: (pl["workspace_bytes"] - 256) / pl["workgroups"]       # 256 B of counters at this size
-    assert abs(per_slot(plans[1]) - 130 * 4) < 1 and abs(per_slot(plans[2]) - 2 * 130 * 4) < 1
-    assert abs(per_slot(plans[4]) - 4 * 130 * 4) < 1
+    per_slot = lambda pl: (pl["workspace_bytes"] - 3840) / pl["workgroups"]      # 3840 B of counters at this size
+    assert abs(per_slot(plans[1]) - 130 * 4) < 2 and abs(per_slot(plans[2]) - 2 * 130 * 4) < 2
+    assert abs(per_slot(plans[4]) - 4 * 130 * 4) < 2
     for bad in (-1, 65):
         d = binding.make_desc(8, 32, 128, 4096, 1, 10, 4096, 0, q_len=bad)
         with pytest.raises(span.SpanAttnError):
@@ -173,9 +175,27 @@ def test_level_batches_with_enough_pairs_are_not_sliced():
     ragged = tok.copy()
     ragged[0] = 1100                                             # one long sequence: slices level the work again
     plan = span.span_plan_query(binding.make_desc(16, 32, 128, 4096, 1, 16, 1100, 0, tokens_per_seq=ragged))
-    assert plan["max_splits"] > 1 and plan["workgroups"] > 1024
+    assert plan["max_splits"] > 1 and 512 < plan["workgroups"] <= 1024
     few = binding.make_desc(8, 32, 128, 4096, 1, 16, int(tok.max()), 0, tokens_per_seq=tok[:8])   # 256 pairs
     assert span.span_plan_query(few)["max_splits"] > 1
+
+
+def test_small_batches_aim_at_a_quarter_round_of_large_slices():
+    """Few, large slices: a quarter of a resident round (512 workgroups), or two slices per sequence on average if
+    that is more, never beyond one round (2048)."""
+    plan = lambda B, tok: span.span_plan_query(binding.make_desc(B, 32, 128, 16384, 1, 10, int(np.max(tok)), 0,
+                                                                 tokens_per_seq=np.asarray(tok, np.int64)))
+    one = plan(1, [8000])
+    assert one["workgroups"] == 512 and one["max_splits"] == 16 and one["slice_tokens"] == 500
+    eight = plan(8, np.linspace(200, 1600, 8))
+    assert 384 < eight["workgroups"] <= 512
+    sixteen = plan(16, np.linspace(110, 1100, 16))
+    assert 768 < sixteen["workgroups"] <= 1024
+    big = plan(32, np.linspace(1000, 8000, 32))
+    assert 1700 < big["workgroups"] <= 2048
+    # without the counts: the same room, spread evenly
+    uni = span.span_plan_query(binding.make_desc(8, 32, 128, 16384, 1, 10, 1600, 0))
+    assert uni["workgroups"] == 512 and uni["max_splits"] == 2
 
 
 def test_validator_matches_oracle_on_golden_cases():

@@ -316,22 +316,6 @@ PAPER_MICROBENCH = {"speedup_vs_hf_geomean": {"32": 0.97, "64": 1.2, "128": 1.6,
                     "source": "paper Sec. 5.2"}
 
 
-def random_mask_spans(batch, length, run, seed, keep=0.5):
-    """Unstructured masks: the context is cut into runs of `run` tokens, each kept with probability `keep`
-    independently (run = 1: every token decides for itself).  Returned as the blocked (block index, bit mask)
-    encoding's interval form."""
-    import numpy as np
-    from workloads import SpanBatch
-    rng = np.random.default_rng(seed)
-    per_seq = []
-    for _ in range(batch):
-        kept = np.repeat(rng.random(-(-length // run)) < keep, run)[:length]
-        kept[-1] = True                                  # the newest token always attends itself
-        edges = np.flatnonzero(np.diff(np.concatenate(([0], kept.view(np.int8), [0]))))
-        per_seq.append(list(zip(edges[0::2].tolist(), edges[1::2].tolist())))
-    return SpanBatch.from_lists(per_seq, np.full(batch, length, dtype=np.int32))
-
-
 def microbench(device, steps, warmup):
     """The kernel micro-benchmark of Sec. 5.2: one new token, batch 64, 1024..8096 cached tokens, random masks that
     keep 50 % of the context in runs of `sparsity block size` tokens.  The masks travel the paper's way: blocked
@@ -341,7 +325,7 @@ def microbench(device, steps, warmup):
     import numpy as np
     import torch
     import paper_2404_09336_amd as span
-    from workloads import DecodeConfig, draw_qkv, full_cover_spans, microbench_spans
+    from workloads import DecodeConfig, draw_qkv, full_cover_spans, microbench_spans, random_mask_spans
     rows, fine_rows, logsum, overhead = [], [], {}, {}
     for L in (1024, 2048, 4096, 8096):
         cfg = DecodeConfig(100, f"microbench-{L}", 64, 32, 128, L, L, "f16", 2e-3)

@@ -21,6 +21,8 @@ VARIANTS = {
     "trace": ["-DSPAN_PHASE_TRACE"],
     # K / V rows fetched with the default cache policy instead of the non-temporal one
     "no_nt": ["-DSPAN_ROW_LOAD_POLICY=0"],
+    # K / V tiles staged through LDS with direct-to-LDS loads before the lanes read their pieces
+    "lds": ["-DSPAN_STAGE_LDS"],
 }
 
 

@@ -355,6 +355,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   __shared__ float s_ml[kWavesPerBlock][NQ][2];
   __shared__ float s_gm[kWavesPerBlock][NQ], s_gl[kWavesPerBlock][NQ];
   __shared__ int s_ticket;
+#ifdef SPAN_STAGE_LDS
+  __shared__ u32x4 s_stage[kWavesPerBlock][2][U][64];  // measurement build: U K tiles and U V tiles of 1 KiB per wave
+#endif
 
   // Query token j of this launch is row (b, q_first + j, h) of q and out; a launch whose last tokens do
   // not exist (q_len not a multiple of NQ) computes them from the last real one and never writes them.
@@ -633,8 +636,25 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
       // returns zeros, and get no weight.
       ok[u] = r < wn && p != new_pos && p <= lim[0];
       const uint32_t off = ok[u] ? (uint32_t)p * ROWB + lane_off : 0xfffffff0u;
+#ifdef SPAN_STAGE_LDS
+      // measurement build: the same rows staged through LDS (direct-to-LDS loads, lane i's 16 bytes land in slot i)
+#if defined(__HIP_DEVICE_COMPILE__)  // (the host pass has no LDS address space to type-check the builtin against)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kslab, &s_stage[wave][0][u][0], 16, off, 0, 0, kRowLoadPolicy);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vslab, &s_stage[wave][1][u][0], 16, off, 0, 0, kRowLoadPolicy);
+#endif
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the tiles are in LDS
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      kr[u] = s_stage[wave][0][u][lane];
+      vr[u] = s_stage[wave][1][u][lane];
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // read out before the next iteration's loads overwrite them
+    {
+#else
       kr[u] = load_row_piece(kslab, off);
       vr[u] = load_row_piece(vslab, off);
+#endif
     }
     float w[NQ][U];  // scores first, then softmax weights
 #pragma unroll

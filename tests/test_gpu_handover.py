@@ -1,0 +1,77 @@
+"""The hand-over of the slices' partial states between workgroups (publish, acknowledge, ticket, last arrival
+re-reads) must never let the merging workgroup see a stale value.  The merge order is fixed, so a sliced call is
+bit-reproducible: thousands of back-to-back calls on ONE workspace must all give the first call's bits, and those
+must agree with the oracle.  A stale read (a state of the previous call, or a half-written one) would show up as
+a differing output row."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2404_09336_amd as span
+from workloads import CONFIGS, DecodeConfig, SpanBatch, draw_qkv, draw_spans, to_host_raw
+
+pytestmark = pytest.mark.gpu
+
+CALLS = 4096
+RING = 16            # output buffers written in turn, compared together
+
+
+def _dev(a, device):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def hammer(cfg, sp, device, what, **plan_kw):
+    tok = sp.tokens_per_seq()
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=device)
+    lists = [_dev(a, device) for a in (sp.offsets, sp.starts, sp.ends, sp.ctx_lens)]
+    kw = dict(max_tokens=int(tok.max()))
+    kw.update(plan_kw)
+    first = span.prepare_span_decode_attn(q, K, V, *lists, np.float32(cfg.scale), **kw)
+    plan = span.span_plan_query(first.desc)
+    assert plan["max_splits"] > 1, plan
+    workspace = first._keepalive[-1]
+    outs = [torch.empty_like(first.out) for _ in range(RING)]
+    calls = [span.prepare_span_decode_attn(q, K, V, *lists, np.float32(cfg.scale), outs[i], workspace=workspace, **kw)
+             for i in range(RING)]
+    want = first().clone()
+    torch.cuda.synchronize()
+    ref = oracle.span_attn(to_host_raw(q), to_host_raw(K), to_host_raw(V), sp.offsets, sp.starts, sp.ends,
+                           np.float32(cfg.scale), dtype=cfg.dtype)
+    assert float(np.abs(want.cpu().numpy().astype(np.float64) - ref).max()) <= cfg.tol
+    done = 0
+    while done < CALLS:
+        for _ in range(8):                      # 8 x RING calls back to back, nothing else on the stream in between
+            for c in calls:
+                c()
+            done += RING
+        differing = sum(int((o != want).sum()) for o in outs)     # (the last RING outputs; earlier ones were overwritten)
+        assert differing == 0, f"{what}: {differing} output elements differ from the first call after {done} calls"
+        for o in outs:
+            o.fill_(float("nan"))
+    print(f"[handover] {what}: {done} calls, {plan['max_splits']} slices per pair at most, {plan['workgroups']} "
+          f"workgroups, runs_in_arguments={plan['runs_in_arguments']}: all outputs bit-identical", flush=True)
+
+
+@pytest.mark.parametrize("cid", [2, 4])
+@pytest.mark.parametrize("host_lists", [False, True])
+def test_sliced_workloads_are_bit_reproducible(cid, host_lists, gpu_device):
+    cfg = CONFIGS[cid]
+    sp = draw_spans(cfg)
+    kw = dict(host_spans=(sp.offsets, sp.starts, sp.ends)) if host_lists else dict(tokens_per_seq=sp.tokens_per_seq())
+    hammer(cfg, sp, gpu_device, f"config {cid}, {'run' if host_lists else 'table'} mode", **kw)
+
+
+def test_one_pair_in_113_slices_is_bit_reproducible(gpu_device):
+    """Every slice of the 113 is a single workgroup of 17 positions: tickets arrive as close together as they can."""
+    cfg = DecodeConfig(98, "handover-113", 2, 8, 128, 2048, 2048, "f16", 2e-3)
+    sp = SpanBatch.from_lists([[(0, 700), (900, 2048)], [(5, 1900)]], [2048, 2048])
+    hammer(cfg, sp, gpu_device, "113 forced slices", num_splits=113)
+
+
+def test_uniform_grid_with_empty_slices_is_bit_reproducible(gpu_device):
+    """Without the token counts short sequences leave slices empty: their slots are never written and must be
+    ignored, not read as the previous call's state."""
+    cfg = CONFIGS[4]
+    sp = draw_spans(cfg)
+    hammer(cfg, sp, gpu_device, "config 4, uniform grid")

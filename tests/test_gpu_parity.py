@@ -309,6 +309,29 @@ def test_unstructured_masks_through_the_blocked_encoding(gpu_device):
     check(run_span(cfg, sp, q, K, V, gpu_device), ref, cfg.tol, "random bit masks via blocked encoding")
 
 
+@pytest.mark.parametrize("L", [1024, 8096])
+@pytest.mark.parametrize("run", [1, 2, 16])
+def test_unstructured_masks_at_microbenchmark_lengths(L, run, gpu_device):
+    """Per-token (run = 1) and short-run random masks at the micro-benchmark's context lengths: up to ~2000
+    intervals per sequence travel through the blocked encoding into the interval kernel (64 intervals per chunk,
+    256 rows per window), with and without the host copies of the lists."""
+    from workloads import random_mask_spans
+    cfg = DecodeConfig(97, f"unstructured-{L}-{run}", 4, 32, 128, L, L, "f16", 2e-3)
+    sp0 = random_mask_spans(cfg.batch, L, run, seed=L + run)
+    boff, bidx, bm = span.span_intervals_to_blocks(256, sp0.offsets, sp0.starts, sp0.ends)
+    off, st, en = span.span_blocks_to_intervals(256, boff, bidx, bm)
+    sp = SpanBatch(off, st, en, sp0.ctx_lens)
+    assert np.array_equal(off, sp0.offsets) and np.array_equal(st, sp0.starts) and np.array_equal(en, sp0.ends)
+    q, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device, seed=L + run)
+    ref = oracle_span(cfg, sp, q, K, V)
+    print(f"[case] L={L} run={run}: {len(st) / cfg.batch:.0f} intervals per sequence", flush=True)
+    check(run_span(cfg, sp, q, K, V, gpu_device), ref, cfg.tol, f"unstructured L={L} run={run}")
+    check(run_span(cfg, sp, q, K, V, gpu_device, host_spans=(off, st, en)), ref, cfg.tol,
+          f"unstructured L={L} run={run}, host lists")
+    check(run_span(cfg, sp, q, K, V, gpu_device, tokens_per_seq=None, num_splits=5), ref, cfg.tol,
+          f"unstructured L={L} run={run}, 5 slices")
+
+
 def test_non_default_stream(gpu_device):
     cfg = small_cfg("f16", 128, B=2, H=4, L=512)
     sp = SpanBatch.from_lists([[(0, 100), (400, 512)], [(7, 300)]], [512, 512])

@@ -145,3 +145,17 @@ def microbench_spans(batch: int, length: int, sparsity_block: int, seed: int, ke
                 iv.append((s, e))
         per_seq.append(iv)
     return SpanBatch.from_lists(per_seq, np.full(batch, length, dtype=np.int32))
+
+
+def random_mask_spans(batch: int, length: int, run: int, seed: int, keep: float = 0.5) -> SpanBatch:
+    """Unstructured masks (the paper's kernel takes any mask, Sec. 5.2): the context is cut into runs of `run`
+    tokens, each kept with probability `keep` independently (run = 1: every token decides for itself); the
+    newest token always attends itself.  Returned as the interval list of the kept positions."""
+    rng = np.random.default_rng(seed)
+    per_seq = []
+    for _ in range(batch):
+        kept = np.repeat(rng.random(-(-length // run)) < keep, run)[:length]
+        kept[-1] = True
+        edges = np.flatnonzero(np.diff(np.concatenate(([0], kept.view(np.int8), [0]))))
+        per_seq.append(list(zip(edges[0::2].tolist(), edges[1::2].tolist())))
+    return SpanBatch.from_lists(per_seq, np.full(batch, length, dtype=np.int32))

@@ -191,17 +191,35 @@ int dense_decode_attn_append(const span_attn_desc_t* desc, const void* q, const 
                              float scale, float* out);
 
 /*
+ * Few-query form of span_decode_attn_append: the desc->q_len new tokens of every sequence (a burst of
+ * reference tokens, or speculated tokens, Sec. 3.2) are appended and attend in one call.  Token j of
+ * sequence b goes to cache row append_pos[b] + j (rows outside [0, max_len) are not written) and attends
+ * the span positions p <= append_pos[b] + j, as in span_decode_attn_multi with q_pos = append_pos.
+ *   q, k_new, v_new : device, desc->dtype, [batch, q_len, heads, head_dim]
+ *   out             : device fp32 [batch, q_len, heads, head_dim]
+ * Within a launch the rows of that launch's tokens are taken from k_new / v_new, never re-read from the
+ * cache; more than four tokens take ceil(q_len / 4) launches on the stream, each appending its own
+ * tokens' rows, which the later ones then read from the cache.
+ */
+int span_decode_attn_multi_append(const span_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                                  void* k_cache, void* v_cache, const int32_t* append_pos,
+                                  const int32_t* span_offsets, const int32_t* span_starts, const int32_t* span_ends,
+                                  float scale, float* out);
+
+/*
  * The step between two decode steps of one group of tokens.  Anchors and references are generated
- * once per group (Sec. 3.2 "Overhead"), so the span is chosen per group: from one token of the group to
- * the next it only gains the token just decoded.  For every sequence b, with p = append_pos[b] the
- * position that token was appended at, on desc->stream:
- *    if position p is in the span and p + 1 is not, the interval ending at p + 1 now ends at p + 2
- *    (the next token will attend itself; its row arrives with the next *_append call);
- *    append_pos[b] = p + 1;  ctx_lens[b] += 1 when ctx_lens is not NULL.
- * Sequences with p < 0 or p + 1 >= max_len (cache full) are left untouched.  All pointers are device
- * memory and are the arrays the next span_decode_attn_append / dense_decode_attn_append call reads, so
- * a decode loop over the group needs no host work between tokens and the pair of calls can be recorded
- * into one HIP graph.  desc supplies batch, max_len, num_intervals and stream.
+ * once per group (Sec. 3.2 "Overhead"), so the span is chosen per group: from one step of the group to
+ * the next it only gains the tokens just decoded.  With n = max(desc->q_len, 1) tokens per step (1 for
+ * the one-token calls, q_len for span_decode_attn_multi_append) and p = append_pos[b] the position the
+ * first of them was appended at, for every sequence b, on desc->stream:
+ *    if an interval ends at p + n (the appended tokens close it) and none of the positions
+ *    p + n .. p + 2n - 1 is in the span yet, that interval now ends at p + 2n (the next step's tokens
+ *    will attend themselves; their rows arrive with the next *_append call);
+ *    append_pos[b] = p + n;  ctx_lens[b] += n when ctx_lens is not NULL.
+ * Sequences with p < 0 or p + 2n > max_len (no room for another step) are left untouched.  All pointers
+ * are device memory and are the arrays the next *_append call reads, so a decode loop over the group
+ * needs no host work between steps and the pair of calls can be recorded into one HIP graph.  desc
+ * supplies batch, max_len, num_intervals, q_len and stream.
  */
 int span_advance(const span_attn_desc_t* desc, const int32_t* span_offsets, const int32_t* span_starts,
                  int32_t* span_ends, int32_t* append_pos, int32_t* ctx_lens);

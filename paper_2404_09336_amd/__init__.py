@@ -4,7 +4,8 @@ CPU or PyTorch fallback — if the library is not built, calls raise."""
 from .binding import (  # noqa: F401
     PreparedCall, SpanAttnError, lib_path, load_library,
     span_decode_attn, dense_decode_attn, span_decode_attn_append, dense_decode_attn_append,
-    span_decode_attn_multi, prepare_span_decode_attn_multi, span_decode_attn_static, prepare_span_decode_attn_static,
+    span_decode_attn_multi, prepare_span_decode_attn_multi, span_decode_attn_multi_append,
+    prepare_span_decode_attn_multi_append, span_decode_attn_static, prepare_span_decode_attn_static,
     span_advance, prepare_span_advance,
     prepare_span_decode_attn, prepare_dense_decode_attn, prepare_span_decode_attn_append,
     prepare_dense_decode_attn_append,

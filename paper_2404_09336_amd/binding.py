@@ -71,6 +71,8 @@ def load_library():
         lib.span_decode_attn_append.restype = ctypes.c_int
         lib.dense_decode_attn_append.argtypes = [DP, P, P, P, P, P, P, P, F, P]
         lib.dense_decode_attn_append.restype = ctypes.c_int
+        lib.span_decode_attn_multi_append.argtypes = [DP, P, P, P, P, P, P, P, P, P, F, P]
+        lib.span_decode_attn_multi_append.restype = ctypes.c_int
         lib.span_advance.argtypes = [DP, P, P, P, P, P]
         lib.span_advance.restype = ctypes.c_int
         lib.span_validate.argtypes = [I32, I32, P, P, P, P, P, P, P]
@@ -148,14 +150,16 @@ def span_workspace_init(desc: _Desc) -> None:
         raise SpanAttnError(rc, "span_workspace_init")
 
 
-def prepare_span_advance(span_offsets, span_starts, span_ends, append_pos, ctx_lens=None, *, max_len, stream=None):
-    """Device int32 tensors; span_ends, append_pos and ctx_lens (optional) are updated in place on the GPU."""
+def prepare_span_advance(span_offsets, span_starts, span_ends, append_pos, ctx_lens=None, *, max_len, stream=None,
+                         q_len=0):
+    """Device int32 tensors; span_ends, append_pos and ctx_lens (optional) are updated in place on the GPU.
+    q_len: tokens appended per step (0 or 1 for the one-token calls)."""
     import torch
     lib = load_library()
     batch, n_int = int(append_pos.numel()), int(span_starts.numel())
     if stream is None:
         stream = torch.cuda.current_stream(append_pos.device).cuda_stream
-    desc = make_desc(batch, 1, 64, int(max_len), SPAN_F32, n_int, stream=stream)
+    desc = make_desc(batch, 1, 64, int(max_len), SPAN_F32, n_int, stream=stream, q_len=q_len)
     args = (ctypes.byref(desc), _i32_dev(span_offsets, batch + 1, "span_offsets"), _i32_dev(span_starts, n_int, "span_starts"),
             _i32_dev(span_ends, n_int, "span_ends"), _i32_dev(append_pos, batch, "append_pos"),
             _i32_dev(ctx_lens, batch, "ctx_lens") if ctx_lens is not None else None)
@@ -163,8 +167,9 @@ def prepare_span_advance(span_offsets, span_starts, span_ends, append_pos, ctx_l
     return PreparedCall("span_advance", lib.span_advance, desc, args, None, keep)
 
 
-def span_advance(span_offsets, span_starts, span_ends, append_pos, ctx_lens=None, *, max_len, stream=None):
-    prepare_span_advance(span_offsets, span_starts, span_ends, append_pos, ctx_lens, max_len=max_len, stream=stream)()
+def span_advance(span_offsets, span_starts, span_ends, append_pos, ctx_lens=None, *, max_len, stream=None, q_len=0):
+    prepare_span_advance(span_offsets, span_starts, span_ends, append_pos, ctx_lens, max_len=max_len, stream=stream,
+                         q_len=q_len)()
 
 
 def span_validate(span_offsets, span_starts, span_ends, ctx_lens):
@@ -446,6 +451,29 @@ def prepare_dense_decode_attn_append(q, k_new, v_new, k_cache, v_cache, append_p
             _i32_dev(ctx_lens, desc.batch, "ctx_lens"), float(scale), out.data_ptr())
     keep = (q, k_new, v_new, k_cache, v_cache, append_pos, ctx_lens, workspace)
     return PreparedCall("dense_decode_attn_append", lib.dense_decode_attn_append, desc, args, out, keep)
+
+
+def prepare_span_decode_attn_multi_append(q, k_new, v_new, k_cache, v_cache, append_pos, span_offsets, span_starts,
+                                          span_ends, scale, out=None, *, max_tokens=0, num_splits=0, workspace=None,
+                                          stream=None, tokens_per_seq=None, host_spans=None) -> PreparedCall:
+    """Few-query append: q, k_new, v_new [B,Q,H,D]; token j of sequence b goes to cache row append_pos[b] + j."""
+    lib = load_library()
+    n_int = int(span_starts.numel())
+    desc, out, workspace = _prepare(q, k_cache, v_cache, out, n_int, max_tokens, num_splits, workspace, stream,
+                                    tokens_per_seq, multi=True, host_spans=host_spans)
+    _check_new_rows(q, k_new, v_new)
+    args = (ctypes.byref(desc), q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), k_cache.data_ptr(),
+            v_cache.data_ptr(), _i32_dev(append_pos, desc.batch, "append_pos"),
+            _i32_dev(span_offsets, desc.batch + 1, "span_offsets"), _i32_dev(span_starts, n_int, "span_starts"),
+            _i32_dev(span_ends, n_int, "span_ends"), float(scale), out.data_ptr())
+    keep = (q, k_new, v_new, k_cache, v_cache, append_pos, span_offsets, span_starts, span_ends, workspace)
+    return PreparedCall("span_decode_attn_multi_append", lib.span_decode_attn_multi_append, desc, args, out, keep)
+
+
+def span_decode_attn_multi_append(q, k_new, v_new, k_cache, v_cache, append_pos, span_offsets, span_starts, span_ends,
+                                  scale, out=None, **kw):
+    return prepare_span_decode_attn_multi_append(q, k_new, v_new, k_cache, v_cache, append_pos, span_offsets,
+                                                 span_starts, span_ends, scale, out, **kw)()
 
 
 def span_decode_attn_append(q, k_new, v_new, k_cache, v_cache, append_pos, span_offsets, span_starts, span_ends,

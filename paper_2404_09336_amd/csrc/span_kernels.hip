@@ -340,9 +340,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   // hides behind the metadata chain).  The row is written into the cache by the first slice's workgroup
   // of each (batch, head) and, in this launch, never read back from the cache: the wave that meets
   // position new_pos in its rows takes it from the copy parked in LDS instead, so the kernel has no race.
-  const int new_pos = a.append_pos ? a.append_pos[b] : -2;  // -2 matches no position
+  // With several query tokens (NQ > 1) every token brings a row, for positions append_pos[b] + token; they are
+  // handled with the rows that only some tokens of the pass see (below) and new_pos stays unused.
+  const bool append_many = NQ > 1 && a.append_pos != nullptr;
+  const int new_pos = (NQ == 1 && a.append_pos) ? a.append_pos[b] : -2;  // -2 matches no position
   u32x4 kn_raw = {0u, 0u, 0u, 0u}, vn_raw = {0u, 0u, 0u, 0u};
-  if (a.append_pos) {
+  if (NQ == 1 && a.append_pos) {
     kn_raw = *reinterpret_cast<const u32x4*>((const char*)a.k_new + bh * ROWB + (uint32_t)lir * 16u);
     vn_raw = *reinterpret_cast<const u32x4*>((const char*)a.v_new + bh * ROWB + (uint32_t)lir * 16u);
   }
@@ -427,10 +430,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     o[j] = 0.f;
   }
   // Append variant: the first slice's workgroup writes the new row into the cache, whatever the span holds.
-  if (a.append_pos && split == 0 && wave == 0 && lane < LPR && new_pos >= 0 && new_pos < a.max_len) {
+  if (NQ == 1 && a.append_pos && split == 0 && wave == 0 && lane < LPR && new_pos >= 0 && new_pos < a.max_len) {
     const size_t row = (bh * (size_t)a.max_len + (size_t)new_pos) * ROWB + (uint32_t)lir * 16u;
     *reinterpret_cast<u32x4*>((char*)a.k + row) = kn_raw;
     *reinterpret_cast<u32x4*>((char*)a.v + row) = vn_raw;
+  }
+  if constexpr (NQ > 1) {  // the rows of this pass's tokens, one token per wave
+    if (append_many && split == 0 && lane < LPR) {
+      for (int i = wave; i < nq_here; i += kWavesPerBlock) {
+        const int pos_i = min(a.append_pos[b], kMaxLen) + a.q_first + i;
+        if (pos_i >= 0 && pos_i < a.max_len) {
+          const size_t src = qrow(i) * ROWB + (uint32_t)lir * 16u;
+          const size_t row = (bh * (size_t)a.max_len + (size_t)pos_i) * ROWB + (uint32_t)lir * 16u;
+          *reinterpret_cast<u32x4*>((char*)a.k + row) = *reinterpret_cast<const u32x4*>((const char*)a.k_new + src);
+          *reinterpret_cast<u32x4*>((char*)a.v + row) = *reinterpret_cast<const u32x4*>((const char*)a.v_new + src);
+        }
+      }
+    }
   }
   if (cnt > 0) {  // same decision in all 4 waves
   // How the slice's rows are dealt to the 4 waves.  My rows are numbered r = 0..nrows-1; row r is
@@ -473,7 +489,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     for (int i = 0; i < EPL; ++i) acc[j][i] = 0.f;
   }
 
-  if (a.append_pos && lane < LPR) {  // park the new row in LDS (frees the registers)
+  if (NQ == 1 && a.append_pos && lane < LPR) {  // park the new row in LDS (frees the registers)
     s_new[wave][0][lane] = kn_raw;
     s_new[wave][1][lane] = vn_raw;
   }
@@ -577,7 +593,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     if (!kDense && w0 > 0) tabulate(std::false_type{}, w0, wn);
   }
 
-  if (a.append_pos) {  // is the appended row one of the window's rows?  Then row group 0 takes it in now.
+  if (NQ == 1 && a.append_pos) {  // is the appended row one of the window's rows?  Then row group 0 takes it in now.
     bool mine = false;
     for (int r = lane; r < wn; r += 64) mine = mine || (kDense ? vrow(w0 + r) : s_pos[wave][r]) == new_pos;
     if (__builtin_amdgcn_ballot_w64(mine) != 0) {  // wave-uniform
@@ -595,20 +611,33 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   // positions of a sequence) are seen by the later tokens only.  The streaming loop below serves the rows every
   // token of the pass sees; these few are taken in here, one at a time, each into the states of exactly the
   // tokens that see it - a hidden row never meets a token's sums, not even with weight zero (0 * Inf).
+  // In the append form the pass's own tokens sit at exactly these positions and at the first token's own: their
+  // rows are not in the cache yet for this launch and come from k_new / v_new instead.
   if constexpr (NQ > 1) {
     if (a.q_pos) {
+      const int first_here = lim[0] + (append_many ? 0 : 1);  // first position the streaming loop leaves out
       for (int r0 = 0; r0 < wn; r0 += 64) {
         const int p = r0 + lane < wn ? s_pos[wave][r0 + lane] : -1;
-        uint64_t todo = __builtin_amdgcn_ballot_w64(p > lim[0] && p <= lim[NQ - 1]);
+        uint64_t todo = __builtin_amdgcn_ballot_w64(p >= first_here && p <= lim[NQ - 1]);
         while (todo != 0) {  // wave-uniform
           const int pb = __builtin_amdgcn_readlane(p, __builtin_ctzll(todo));
           todo &= todo - 1;
-          const uint32_t off = (uint32_t)pb * ROWB + lane_off;  // every row group fetches the same row
-          const u32x4 kb = load_row_piece(kslab, off), vb = load_row_piece(vslab, off);
+          u32x4 kb, vb;  // every row group fetches the same row
+          if (append_many) {
+            const int i = pb - lim[0];     // the token that brought this row
+            if (i >= nq_here) continue;    // (a padded pass: no such token, and no token that could see it)
+            const size_t src = qrow(i) * ROWB + lane_off;
+            kb = *reinterpret_cast<const u32x4*>((const char*)a.k_new + src);
+            vb = *reinterpret_cast<const u32x4*>((const char*)a.v_new + src);
+          } else {
+            const uint32_t off = (uint32_t)pb * ROWB + lane_off;
+            kb = load_row_piece(kslab, off);
+            vb = load_row_piece(vslab, off);
+          }
           float vf[EPL];
           Elt::unpack(vb, vf);
 #pragma unroll
-          for (int j = 1; j < NQ; ++j) {
+          for (int j = 0; j < NQ; ++j) {
             const float d = group_allreduce_sum<LPR>(Elt::dot(kb, qv[j])) * post;
             if (pb <= lim[j] && grp == 0) {
               const float l_one = 1.f;
@@ -634,7 +663,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
       // holds there: Sec. 2.2, mask paragraph; the few rows that only later tokens of the pass see were
       // taken in above).  They request an offset past the slab instead, for which the buffer hardware
       // returns zeros, and get no weight.
-      ok[u] = r < wn && p != new_pos && p <= lim[0];
+      ok[u] = r < wn && p != new_pos && p <= lim[0] && !(append_many && p == lim[0]);
       const uint32_t off = ok[u] ? (uint32_t)p * ROWB + lane_off : 0xfffffff0u;
 #ifdef SPAN_STAGE_LDS
       // measurement build: the same rows staged through LDS (direct-to-LDS loads, lane i's 16 bytes land in slot i)
@@ -852,25 +881,26 @@ __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, size_t n) 
   if (i < n) p[i] = 0u;
 }
 
-// One thread per sequence: the span gains the position after the one just appended (see span_advance).
-__global__ __launch_bounds__(256) void advance_kernel(int batch, int max_len, int num_intervals, const int32_t* offsets,
-                                                      const int32_t* starts, int32_t* ends, int32_t* append_pos,
-                                                      int32_t* ctx_lens) {
+// One thread per sequence: the span gains the positions after the ones just appended (see span_advance).
+__global__ __launch_bounds__(256) void advance_kernel(int batch, int max_len, int num_intervals, int count,
+                                                      const int32_t* offsets, const int32_t* starts, int32_t* ends,
+                                                      int32_t* append_pos, int32_t* ctx_lens) {
   const int b = blockIdx.x * 256 + threadIdx.x;
   if (b >= batch) return;
   const int p = append_pos[b];
-  if (p < 0 || p + 1 >= max_len) return;
+  if (p < 0 || (long long)p + 2 * (long long)count > (long long)max_len) return;
+  const int next = p + count;  // first position of the next step's tokens; they take next .. next + count - 1
   const int lo = clampi(offsets[b], 0, num_intervals), hi = clampi(offsets[b + 1], lo, num_intervals);
-  int grow = -1;        // interval that ends right after p
-  bool taken = false;   // p + 1 is already inside some interval
+  int grow = -1;        // interval that ends right after the appended tokens
+  bool taken = false;   // some of the next positions are already inside an interval
   for (int i = lo; i < hi; ++i) {
     const int st = starts[i], en = ends[i];
-    if (st < en && en == p + 1) grow = i;
-    if (st <= p + 1 && p + 1 < en) taken = true;
+    if (st < en && en == next) grow = i;
+    if (st < en && st < next + count && next < en) taken = true;
   }
-  if (grow >= 0 && !taken) ends[grow] = p + 2;
-  append_pos[b] = p + 1;
-  if (ctx_lens) ctx_lens[b] += 1;
+  if (grow >= 0 && !taken) ends[grow] = next + count;
+  append_pos[b] = next;
+  if (ctx_lens) ctx_lens[b] += count;
 }
 
 thread_local int g_last_hip_error = 0;
@@ -1106,6 +1136,16 @@ extern "C" int span_decode_attn_append(const span_attn_desc_t* desc, const void*
                                  k_new, v_new, append_pos);
 }
 
+extern "C" int span_decode_attn_multi_append(const span_attn_desc_t* desc, const void* q, const void* k_new,
+                                             const void* v_new, void* k_cache, void* v_cache,
+                                             const int32_t* append_pos, const int32_t* span_offsets,
+                                             const int32_t* span_starts, const int32_t* span_ends, float scale,
+                                             float* out) {
+  if (!k_new || !v_new || !append_pos) return SPAN_ERR_NULL;
+  return spanattn::launch<false>(desc, q, k_cache, v_cache, span_offsets, span_starts, span_ends, nullptr, scale, out,
+                                 k_new, v_new, append_pos, append_pos, true);
+}
+
 extern "C" int dense_decode_attn_append(const span_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
                                         void* k_cache, void* v_cache, const int32_t* append_pos,
                                         const int32_t* ctx_lens, float scale, float* out) {
@@ -1120,8 +1160,8 @@ extern "C" int span_advance(const span_attn_desc_t* desc, const int32_t* span_of
   if (rc != SPAN_OK) return rc;
   if (!span_offsets || !append_pos || (desc->num_intervals > 0 && (!span_starts || !span_ends))) return SPAN_ERR_NULL;
   hipLaunchKernelGGL(spanattn::advance_kernel, dim3((unsigned)((desc->batch + 255) / 256)), dim3(256), 0,
-                     (hipStream_t)desc->stream, desc->batch, desc->max_len, desc->num_intervals, span_offsets,
-                     span_starts, span_ends, append_pos, ctx_lens);
+                     (hipStream_t)desc->stream, desc->batch, desc->max_len, desc->num_intervals,
+                     spanattn::query_tokens(desc), span_offsets, span_starts, span_ends, append_pos, ctx_lens);
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) {
     spanattn::g_last_hip_error = (int)err;

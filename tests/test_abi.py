@@ -28,7 +28,8 @@ def test_library_exports_every_declared_symbol():
     assert {"span_decode_attn", "dense_decode_attn", "span_validate", "span_plan_query", "span_workspace_bytes",
             "span_workspace_init", "span_strerror", "span_last_hip_error", "span_blocks_to_intervals",
             "span_intervals_to_blocks", "span_build", "span_decode_attn_append", "dense_decode_attn_append",
-            "span_decode_attn_multi", "span_advance", "span_decode_attn_static"} <= set(names)
+            "span_decode_attn_multi", "span_advance", "span_decode_attn_static",
+            "span_decode_attn_multi_append"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 

@@ -56,6 +56,62 @@ def test_oracle_advance_is_the_set_definition():
             assert all(a < e for a, e in iv) and sum(e - a for a, e in iv) == len(after)
 
 
+def test_oracle_advance_by_several_tokens_is_the_set_definition():
+    """n tokens per step: the interval the appended tokens closed grows by the next n positions, if all are free."""
+    rng = np.random.default_rng(24)
+    L = 60
+    for trial in range(600):
+        n = int(rng.integers(2, 6))
+        B = int(rng.integers(1, 4))
+        per_seq = _random_lists(rng, B, L)
+        sp = SpanBatch.from_lists(per_seq, np.full(B, L, np.int32))
+        off, st, en = sp.offsets.tolist(), sp.starts.tolist(), sp.ends.tolist()
+        pos = []
+        for b in range(B):       # often such that the appended tokens end an interval
+            ends_b = [e - n for _, e in per_seq[b]]
+            pos.append(int(rng.choice(ends_b)) if rng.random() < 0.7 else int(rng.integers(-2, L + 1)))
+        before = [_positions(sp.intervals(b)) for b in range(B)]
+        pos2 = list(pos)
+        oracle_advance(off, st, en, pos2, None, L, count=n)
+        for b in range(B):
+            after = _positions(zip(st[off[b]:off[b + 1]], en[off[b]:off[b + 1]]))
+            p = pos[b]
+            if p < 0 or p + 2 * n > L:
+                assert after == before[b] and pos2[b] == p
+                continue
+            nxt = set(range(p + n, p + 2 * n))
+            closes = any(e == p + n for _, e in per_seq[b])
+            want = before[b] | nxt if (closes and not (nxt & before[b])) else before[b]
+            assert after == want, (per_seq[b], p, n)
+            assert pos2[b] == p + n
+            iv = list(zip(st[off[b]:off[b + 1]], en[off[b]:off[b + 1]]))
+            assert all(a < e for a, e in iv) and sum(e - a for a, e in iv) == len(after)
+
+
+@pytest.mark.gpu
+def test_kernel_advances_by_several_tokens_like_the_oracle(gpu_device):
+    import paper_2404_09336_amd as span
+    rng = np.random.default_rng(25)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(gpu_device)
+    for trial in range(20):
+        n = int(rng.integers(2, 9))
+        B, L = int(rng.integers(1, 400)), int(rng.choice([64, 500, 4096]))
+        per_seq = _random_lists(rng, B, L)
+        sp = SpanBatch.from_lists(per_seq, np.full(B, L, np.int32))
+        pos = np.array([(per_seq[b][int(rng.integers(len(per_seq[b])))][1] - n) if rng.random() < 0.7
+                        else int(rng.integers(-2, L + 1)) for b in range(B)], np.int32)
+        ctx = np.maximum(pos + n, 0).astype(np.int32)
+        off, st, en = sp.offsets.tolist(), sp.starts.tolist(), sp.ends.tolist()
+        pos_o, ctx_o = pos.tolist(), ctx.tolist()
+        d_off, d_st, d_en, d_pos, d_ctx = dev(sp.offsets), dev(sp.starts), dev(sp.ends), dev(pos), dev(ctx)
+        for step in range(3):
+            oracle_advance(off, st, en, pos_o, ctx_o, L, count=n)
+            span.span_advance(d_off, d_st, d_en, d_pos, d_ctx, max_len=L, q_len=n)
+            torch.cuda.synchronize()
+            assert d_en.cpu().tolist() == en and d_pos.cpu().tolist() == pos_o, (trial, step, n)
+        assert d_ctx.cpu().tolist() == ctx_o and d_st.cpu().tolist() == st
+
+
 @pytest.mark.gpu
 def test_kernel_matches_oracle_bit_for_bit(gpu_device):
     import paper_2404_09336_amd as span

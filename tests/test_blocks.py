@@ -112,3 +112,37 @@ def test_capacity_is_reported():
     vp = lambda a: ctypes.c_void_p(a.ctypes.data)
     rc = lib.span_blocks_to_intervals(1, 32, vp(boff), vp(bidx), vp(masks), 2, vp(off), vp(st), vp(en), vp(need))
     assert rc == -6 and need[0] == 4 and off.tolist() == [0, 4] and st.tolist() == [0, 2]
+
+
+def _load_word_fixture():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "blocked_encoding_words.txt")
+    cases = []
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        bs, pos, idx, words = [part.split() for part in line.split("|")]
+        bs = int(bs[0])
+        masks = np.array([int(w, 16) for w in words], dtype=np.uint32).reshape(len(idx), bs // 32)
+        cases.append((bs, sorted(int(p) for p in pos), [int(i) for i in idx], masks))
+    return cases
+
+
+def test_bit_order_against_hand_written_words():
+    """The word-level layout (bit t of a block in word t / 32 at bit t % 32) against masks written out by hand:
+    the library's two converters and the set-based reference must all agree with the fixture."""
+    cases = _load_word_fixture()
+    assert len(cases) >= 8
+    for bs, pos, idx, masks in cases:
+        runs = ref.maximal_runs(set(pos))
+        off = [0, len(runs)]
+        st, en = [a for a, _ in runs], [e for _, e in runs]
+        boff, bidx, bm = span.span_intervals_to_blocks(bs, off, st, en)
+        assert bidx.tolist() == idx and boff.tolist() == [0, len(idx)], (bs, pos)
+        assert np.array_equal(bm, masks), (bs, pos, [hex(int(w)) for w in bm.reshape(-1)])
+        off2, st2, en2 = span.span_blocks_to_intervals(bs, [0, len(idx)], idx, masks)
+        assert list(zip(st2.tolist(), en2.tolist())) == runs
+        assert ref.positions_from_blocks(bs, idx, masks) == set(pos)
+        ridx, rmasks = ref.blocks_from_positions(bs, set(pos))
+        assert ridx == idx and np.array_equal(rmasks, masks)

@@ -62,11 +62,26 @@ def test_sliced_workloads_are_bit_reproducible(cid, host_lists, gpu_device):
     hammer(cfg, sp, gpu_device, f"config {cid}, {'run' if host_lists else 'table'} mode", **kw)
 
 
-def test_one_pair_in_113_slices_is_bit_reproducible(gpu_device):
-    """Every slice of the 113 is a single workgroup of 17 positions: tickets arrive as close together as they can."""
-    cfg = DecodeConfig(98, "handover-113", 2, 8, 128, 2048, 2048, "f16", 2e-3)
+@pytest.mark.parametrize("heads", [8, 3])
+def test_one_pair_in_113_slices_is_bit_reproducible(heads, gpu_device):
+    """Every slice of the 113 is a single workgroup of 17 positions: tickets arrive as close together as they can.
+    Consecutive workgroups go to consecutive XCDs (8 of them, each with its own L2), heads varying fastest: with 8
+    heads all slices of a pair share one XCD, with 3 heads they are spread over all eight, so the states really
+    cross L2s on their way to the merging workgroup."""
+    cfg = DecodeConfig(98, f"handover-113-{heads}", 2, heads, 128, 2048, 2048, "f16", 2e-3)
     sp = SpanBatch.from_lists([[(0, 700), (900, 2048)], [(5, 1900)]], [2048, 2048])
-    hammer(cfg, sp, gpu_device, "113 forced slices", num_splits=113)
+    hammer(cfg, sp, gpu_device, f"113 forced slices, {heads} heads", num_splits=113)
+
+
+def test_slices_spread_over_all_xcds_are_bit_reproducible(gpu_device):
+    """A ragged batch with 5 heads (not a multiple of the 8 XCDs): the slices of one pair run on different XCDs."""
+    cfg = DecodeConfig(99, "handover-5-heads", 6, 5, 128, 4096, 4096, "bf16", 2e-3)
+    rng = np.random.default_rng(99)
+    from workloads import place_disjoint
+    per_seq = [place_disjoint(rng, rng.integers(50, 700, size=4), 0, 4096) for _ in range(cfg.batch)]
+    sp = SpanBatch.from_lists(per_seq, np.full(cfg.batch, 4096, np.int32))
+    hammer(cfg, sp, gpu_device, "6 sequences x 5 heads, table mode", tokens_per_seq=sp.tokens_per_seq())
+    hammer(cfg, sp, gpu_device, "6 sequences x 5 heads, 9 slices each", num_splits=9)
 
 
 def test_uniform_grid_with_empty_slices_is_bit_reproducible(gpu_device):

@@ -488,14 +488,16 @@ def pmc_summary(dirs):
 
 
 def read_traffic(cfg_id):
-    """HBM bytes per call measured offline with rocprofv3 --pmc (see profiles/); None if not recorded."""
+    """(HBM bytes per call measured offline with rocprofv3 --pmc, the commit they were measured at), see profiles/;
+    (None, None) if not recorded."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     if not os.path.exists(path):
-        return None
+        return None, None
     try:
-        return json.load(open(path)).get(f"config{cfg_id}", {}).get("hbm_bytes_per_call")
+        doc = json.load(open(path))
+        return doc.get(f"config{cfg_id}", {}).get("hbm_bytes_per_call"), doc.get("measured_at_commit")
     except (ValueError, OSError):
-        return None
+        return None, None
 
 
 def source_revision():
@@ -582,7 +584,8 @@ def main():
                    "source_revision": source_revision()},
         "roofline": {"bound": "hbm", "achieved": round(main_res["gbps_event"], 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(main_res["gbps_event"] / HBM_PEAK_GBPS, 4),
-                     "traffic": read_traffic(cfg.cfg_id) if res_span else None,
+                     "traffic": read_traffic(cfg.cfg_id)[0] if res_span else None,
+                     "traffic_measured_at_commit": read_traffic(cfg.cfg_id)[1] if res_span else None,
                      "us_per_call_hip_events": round(main_res["us_per_call_event"], 3)},
         "paper_context": PAPER_CONTEXT,
     }

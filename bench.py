@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--copies", type=int, default=0, help="independent KV copies to rotate over (0 = auto)")
     ap.add_argument("--coverage", type=float, default=None, help="config 5 only: uniform span coverage")
     ap.add_argument("--num-splits", type=int, default=0)
+    ap.add_argument("--q-len", type=int, default=1,
+                    help="with --only span or --phase-trace: time / trace the few-query call with this many new tokens "
+                         "per sequence instead of the decode step (diagnostic; the bytes counted stay the span's K / V)")
     ap.add_argument("--uniform-grid", action="store_true",
                     help="do not pass per-sequence token counts (every sequence gets the same number of slices)")
     ap.add_argument("--no-host-lists", action="store_true",
@@ -86,7 +89,7 @@ class Workload:
     (q, K, V) tensors of an earlier workload of the same shape and seeds (the spans are drawn anew)."""
 
     def __init__(self, cfg, copies, device, coverage=None, num_splits=0, exact=True, kv=None, spans=None,
-                 host_lists=True):
+                 host_lists=True, q_len=1):
         import numpy as np
         import torch
         import paper_2404_09336_amd as span
@@ -116,6 +119,9 @@ class Workload:
             self.coverages.append(sp.coverage())
             if c == 0:
                 self.host.append((sp, q, K, V))
+        self.one_query_calls, self.q_len = self.span_calls, q_len
+        if q_len > 1:          # diagnostic runs of the few-query call: it takes the place of the span call
+            self.span_calls = few_query_calls(self, q_len, device)
         self.plan = span.span_plan_query(self.span_calls[0].desc)
         self.coverage = sum(self.coverages) / len(self.coverages)
 
@@ -190,6 +196,23 @@ def compact_row(wl, steps, dense_steps=None, rounds=3):
             "slices_per_pair": wl.plan["max_splits"], "workgroups": wl.plan["workgroups"]}
 
 
+def few_query_calls(wl, q_len, device):
+    """Prepared few-query calls on the workload's tensors: the new tokens are the last q_len cache rows."""
+    import numpy as np
+    import torch
+    import paper_2404_09336_amd as span
+    from workloads import draw_queries
+    calls = []
+    for c, one in enumerate(wl.one_query_calls):
+        _, K, V, off, st, en, ctx, _ = one._keepalive
+        q = draw_queries(wl.cfg, q_len, seed=wl.cfg.seed(c), device=device)
+        q_pos = (ctx - q_len).to(torch.int32)
+        calls.append(span.prepare_span_decode_attn_multi(q, K, V, off, st, en, q_pos, np.float32(wl.cfg.scale),
+                                                         max_tokens=one.desc.max_tokens,
+                                                         tokens_per_seq=getattr(one.desc, "_tokens_keepalive", None)))
+    return calls
+
+
 def few_query_table(wl, device, steps, single_us):
     """The few-query entry point on the same workload: q_len new tokens per sequence share one pass over the span
     (each under its causal limit).  Reports the time per call and per token next to the one-token call."""
@@ -198,21 +221,14 @@ def few_query_table(wl, device, steps, single_us):
     import paper_2404_09336_amd as span
     from workloads import draw_queries
     cfg, table = wl.cfg, {}
-    for q_len in (2, 4, 8):
-        calls = []
-        for c, one in enumerate(wl.span_calls):
-            _, K, V, off, st, en, ctx, _ = one._keepalive
-            q = draw_queries(cfg, q_len, seed=cfg.seed(c), device=device)
-            q_pos = (ctx - q_len).to(torch.int32)            # the new tokens are the last q_len cache rows
-            calls.append(span.prepare_span_decode_attn_multi(q, K, V, off, st, en, q_pos, np.float32(cfg.scale),
-                                                             max_tokens=one.desc.max_tokens,
-                                                             tokens_per_seq=getattr(one.desc, "_tokens_keepalive", None)))
+    for q_len in (2, 4, 8, 16, 32):
+        calls = few_query_calls(wl, q_len, device)
         r = timed_loop(calls, wl.span_bytes, steps, max(5, steps // 10), 3)
         us = r["us_per_call_event"]
         table[f"q_len_{q_len}"] = {"us_per_call": round(us, 2), "us_per_token": round(us / q_len, 2),
                                    "tokens_per_s": round(cfg.batch * q_len / us * 1e6, 0),
                                    "speedup_per_token_vs_one_query": round(single_us * q_len / us, 3),
-                                   "passes_over_span": -(-q_len // 4)}
+                                   "passes_over_span": -(-q_len // span.span_plan_query(calls[0].desc)["queries_per_pass"])}
     return table
 
 
@@ -269,8 +285,8 @@ def secondary_bytes(wl):
     cfg, plan = wl.cfg, wl.plan
     sp = wl.host[0][0]
     pairs = cfg.batch * cfg.heads
-    partial = 2 * plan["workgroups"] * (cfg.head_dim + 2) * 4 if plan["max_splits"] > 1 else 0
-    return {"q": pairs * cfg.head_dim * cfg.elt_bytes, "out": pairs * cfg.head_dim * 4,
+    partial = 2 * plan["workgroups"] * plan["queries_per_pass"] * (cfg.head_dim + 2) * 4 if plan["max_splits"] > 1 else 0
+    return {"q": wl.q_len * pairs * cfg.head_dim * cfg.elt_bytes, "out": wl.q_len * pairs * cfg.head_dim * 4,
             "span_metadata": 8 * int(sp.starts.size) + 4 * (cfg.batch + 1),
             "partial_states_write_plus_read": partial}
 
@@ -408,7 +424,7 @@ def phase_trace(args, device):
     lib.span_debug_set_trace.restype = None
     cfg = CONFIGS[args.config]
     wl = Workload(cfg, args.copies or auto_copies(cfg), device, coverage=args.coverage, num_splits=args.num_splits,
-                  exact=not args.uniform_grid, host_lists=not args.no_host_lists)
+                  exact=not args.uniform_grid, host_lists=not args.no_host_lists, q_len=args.q_len)
     calls = wl.span_calls if args.only != "dense" else wl.dense_calls
     wgs = max(span.span_plan_query(c.desc)["workgroups"] for c in calls)
     buf = torch.zeros((wgs, 16), dtype=torch.int64, device=device)
@@ -538,8 +554,11 @@ def main():
 
     cfg = CONFIGS[args.config]
     copies = args.copies or auto_copies(cfg)
+    if args.q_len > 1 and args.only != "span":
+        print("bench.py: --q-len needs --only span (or --phase-trace)", file=sys.stderr)
+        sys.exit(2)
     wl = Workload(cfg, copies, device, coverage=args.coverage, num_splits=args.num_splits,
-                  exact=not args.uniform_grid, host_lists=not args.no_host_lists)
+                  exact=not args.uniform_grid, host_lists=not args.no_host_lists, q_len=args.q_len)
 
     if args.calibrate_copy:
         # a plain elementwise kernel that reads 1 GiB and writes 1 GiB (torch's same-dtype copy_ is a DMA
@@ -575,7 +594,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg.cfg_id} ({cfg.name}): batch {cfg.batch}, {cfg.heads} heads x "
-                               f"{cfg.head_dim}, KV length {cfg.min_len}-{cfg.max_len}, 1 query token",
+                               f"{cfg.head_dim}, KV length {cfg.min_len}-{cfg.max_len}, {args.q_len} query token"
+                               + ("s (few-query call)" if args.q_len > 1 else ""),
                    "storage_dtype": cfg.dtype, "arithmetic": "fp32 multiply-accumulate, fp32 softmax, fp32 output",
                    "span_coverage": round(wl.coverage, 4),
                    "span_bytes_per_call": int(main_res["bytes_per_call"]),
@@ -584,8 +604,8 @@ def main():
                    "source_revision": source_revision()},
         "roofline": {"bound": "hbm", "achieved": round(main_res["gbps_event"], 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(main_res["gbps_event"] / HBM_PEAK_GBPS, 4),
-                     "traffic": read_traffic(cfg.cfg_id)[0] if res_span else None,
-                     "traffic_measured_at_commit": read_traffic(cfg.cfg_id)[1] if res_span else None,
+                     "traffic": read_traffic(cfg.cfg_id)[0] if res_span and args.q_len == 1 else None,
+                     "traffic_measured_at_commit": read_traffic(cfg.cfg_id)[1] if res_span and args.q_len == 1 else None,
                      "us_per_call_hip_events": round(main_res["us_per_call_event"], 3)},
         "paper_context": PAPER_CONTEXT,
     }

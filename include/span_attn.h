@@ -259,6 +259,8 @@ typedef struct span_plan_info {
   int64_t workspace_bytes; /* same value as span_workspace_bytes()                                */
   int32_t runs_in_arguments; /* 1: host_span_* were given and the plan fits: the slices' position runs
                               travel in the kernel arguments (span form)                          */
+  int32_t queries_per_pass;  /* query tokens one launch serves (1, 2, 4 or 16): a call with q_len tokens
+                              launches ceil(q_len / queries_per_pass) passes over the span        */
 } span_plan_info_t;
 int span_plan_query(const span_attn_desc_t* desc, span_plan_info_t* info);
 

@@ -34,12 +34,12 @@ class _Desc(ctypes.Structure):
 class PlanInfo(ctypes.Structure):
     _fields_ = [("exact", ctypes.c_int32), ("slice_tokens", ctypes.c_int32), ("max_splits", ctypes.c_int32),
                 ("slice_limit", ctypes.c_int32), ("workgroups", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64),
-                ("runs_in_arguments", ctypes.c_int32)]
+                ("runs_in_arguments", ctypes.c_int32), ("queries_per_pass", ctypes.c_int32)]
 
     def as_dict(self):
         return {"exact": bool(self.exact), "slice_tokens": self.slice_tokens, "max_splits": self.max_splits,
                 "slice_limit": self.slice_limit, "workgroups": self.workgroups, "workspace_bytes": self.workspace_bytes,
-                "runs_in_arguments": bool(self.runs_in_arguments)}
+                "runs_in_arguments": bool(self.runs_in_arguments), "queries_per_pass": int(self.queries_per_pass)}
 
 
 def lib_path() -> str:

@@ -62,17 +62,24 @@ int check_desc(const span_attn_desc_t* d) {
 
 int32_t query_tokens(const span_attn_desc_t* d) { return d->q_len > 1 ? d->q_len : 1; }
 
-// Query tokens one launch serves: 1, 2 or 4 (the kernel's register budget stops there).
+// Query tokens one launch serves: 1, 2 or 4 on the vector units (their register budget stops there), 16 on the
+// matrix cores (16-bit types with head_dim 128).  The matrix pass takes over from three tokens: measured on
+// batch 64 x ~155 attended positions, 32 heads, fp16: 3 tokens 31.9 us against 37.7 us for the four-token vector
+// pass, 2 tokens 31.5 against 29.7; batch 8 x 300..2000 positions: 27.5 against 29.4 and 27.4 against 25.0.
+#ifndef SPAN_MATRIX_PASS_FROM
+#define SPAN_MATRIX_PASS_FROM 3
+#endif
 static int32_t queries_per_pass(const span_attn_desc_t* d) {
   const int32_t n = query_tokens(d);
+  if (n >= SPAN_MATRIX_PASS_FROM && d->dtype != SPAN_F32 && d->head_dim == 128) return 16;
   return n >= 3 ? 4 : n;
 }
 
 // Workgroups of one resident round: the kernel for one query token runs 8 workgroups per CU, the one for
-// two tokens 6 and the one for four tokens 4 (their register budgets).
+// two tokens 6, the ones for four and for sixteen tokens 4 (their register budgets).
 static int64_t target_workgroups(const span_attn_desc_t* d) {
   const int32_t nq = queries_per_pass(d);
-  return nq == 1 ? kTargetWorkgroups : (nq == 2 ? kTargetWorkgroups * 3 / 4 : kTargetWorkgroups / 2);
+  return nq == 1 ? kTargetWorkgroups : kTargetWorkgroups * (nq == 2 ? 6 : 4) / 8;
 }
 
 static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -328,6 +335,7 @@ extern "C" int span_plan_query(const span_attn_desc_t* desc, span_plan_info_t* i
   spanattn::RunTables runs;
   const spanattn::Partition p = spanattn::plan_partition(desc, nullptr, &runs);
   info->runs_in_arguments = p.runs ? 1 : 0;
+  info->queries_per_pass = p.queries_per_pass;
   info->exact = p.even ? 1 : 0;
   info->slice_tokens = p.slice_tokens;
   info->max_splits = p.num_splits;

@@ -61,7 +61,7 @@ struct Partition {
   int32_t slice_tokens;  // attended positions per slice (exact: upper bound)
   int32_t max_tokens;    // bound on attended positions per sequence
   int32_t total_slices;  // exact: table entries (grid.y); uniform: batch * num_splits
-  int32_t queries_per_pass;  // query tokens one launch serves (1, 2 or 4)
+  int32_t queries_per_pass;  // query tokens one launch serves (1, 2, 4 or 16)
   int32_t granule;       // exact: sequence b is cut into ceil(n_b / granule) slices
   bool runs;             // the slices' position runs were resolved on the host (RunTables filled)
 };

@@ -44,6 +44,11 @@ namespace spanattn {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
@@ -153,6 +158,7 @@ constexpr int kTraceStamps = 16;
 struct F32 {
   static constexpr int kBytes = 4, kPerVec = 4;
   static constexpr bool kPostScale = false;
+  static constexpr bool kHasMfma = false;  // (the sixteen-query pass exists for the 16-bit types)
   struct Q {
     float f[4];
   };
@@ -182,7 +188,24 @@ struct F32 {
 struct F16 {
   static constexpr int kBytes = 2, kPerVec = 8;
   static constexpr bool kPostScale = true;
+  static constexpr bool kHasMfma = true;
+  static constexpr uint32_t kExponent = 0x7c00u;  // all ones: infinity or NaN
   typedef u32x4 Q;
+  // C (16x16, fp32) += A (16x16) * B (16x16): four 16-bit elements of A and of B per lane, two dwords each
+  static __device__ __forceinline__ f32x4 mfma(u32x2 a, u32x2 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, a), __builtin_bit_cast(f16x4, b), c, 0, 0, 0);
+  }
+  // p (fp32, >= 0) as hi + lo in the storage type: hi is p rounded, lo the rounded remainder (together ~22 bits)
+  static __device__ __forceinline__ void split(const float* p, u32x2& hi, u32x2& lo) {
+    f16x4 h, r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      h[i] = (_Float16)p[i];
+      r[i] = (_Float16)(p[i] - (float)h[i]);
+    }
+    hi = __builtin_bit_cast(u32x2, h);
+    lo = __builtin_bit_cast(u32x2, r);
+  }
   static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -206,7 +229,26 @@ struct F16 {
 struct BF16 {
   static constexpr int kBytes = 2, kPerVec = 8;
   static constexpr bool kPostScale = true;
+  static constexpr bool kHasMfma = true;
+  static constexpr uint32_t kExponent = 0x7f80u;
   typedef u32x4 Q;
+  static __device__ __forceinline__ f32x4 mfma(u32x2 a, u32x2 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(i16x4, a), __builtin_bit_cast(i16x4, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint32_t to_bf16(float x) {  // round to nearest even (x finite, >= 0 here)
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  }
+  static __device__ __forceinline__ void split(const float* p, u32x2& hi, u32x2& lo) {
+    uint32_t h[4], r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      h[i] = to_bf16(p[i]);
+      r[i] = to_bf16(p[i] - __builtin_bit_cast(float, h[i] << 16));
+    }
+    hi = u32x2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+    lo = u32x2{r[0] | (r[1] << 16), r[2] | (r[3] << 16)};
+  }
   static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -267,6 +309,12 @@ __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? l
 // K / V rows are fetched with raw buffer loads: the descriptor covers exactly one (batch, head) slab,
 // so the hardware itself returns zeros for any offset outside it, and the cache policy is explicit.
 // Non-temporal (streaming) loads: every row is used once; measured 17 % faster than default-policy loads.
+#ifndef SPAN_MQ_WAVES
+#define SPAN_MQ_WAVES 4
+#endif
+#ifndef SPAN_MQ_TILES
+#define SPAN_MQ_TILES 1
+#endif
 #ifndef SPAN_ROW_LOAD_POLICY
 #define SPAN_ROW_LOAD_POLICY 2  // (a measurement build overrides it to time the other policies)
 #endif
@@ -302,8 +350,14 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int 
 // ---- the streaming kernel ------------------------------------------------------------------------
 // NQ query tokens per sequence are served by one pass over the span's rows (NQ = 1: the decode step proper).
 // The register budget is 64 per lane for one query (8 waves per SIMD), 80 for two (6) and 128 for four (4).
+//
+// NQ = 16 (16-bit types, D = 128) is a dense contraction and runs on the matrix cores: a wave takes its rows in
+// tiles of 16, scores S^T = K Q^T and outputs O^T = V^T P^T are 16x16x16 MFMAs, the running sums stay in the
+// accumulator layout (168 registers, 3 waves per SIMD).
+constexpr int waves_per_simd(int nq) { return nq == 1 ? 8 : (nq == 2 ? 6 : (nq == 4 ? 4 : SPAN_MQ_WAVES)); }
+
 template <class Elt, int D, bool kDense, int U, int NQ, class Args>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 1 ? 8 : (NQ == 2 ? 6 : 4), NQ == 1 ? 8 : (NQ == 2 ? 6 : 4)))) void decode_kernel(
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(waves_per_simd(NQ), waves_per_simd(NQ)))) void decode_kernel(
     const Args a) {
   constexpr int EPL = Elt::kPerVec;        // elements per lane (one 128-bit piece)
   constexpr int LPR = D / EPL;             // lanes per row
@@ -350,13 +404,36 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     vn_raw = *reinterpret_cast<const u32x4*>((const char*)a.v_new + bh * ROWB + (uint32_t)lir * 16u);
   }
 
-  __shared__ int s_pos[kWavesPerBlock][kWin];
-  __shared__ u32x4 s_new[kWavesPerBlock][2][LPR];  // append variant: the new K / V row, parked until its owner needs it
-  __shared__ int s_pref[kWavesPerBlock][64];
-  __shared__ int s_start[kWavesPerBlock][64];
-  __shared__ float s_acc[kWavesPerBlock][NQ][D];
+  // Tables of the streaming phase and the waves' states of the merge phase.  The sixteen-query pass overlays the
+  // two (a barrier separates the phases there), which keeps it at four workgroups per CU.
+  constexpr int kAccPad = NQ == 16 ? 4 : 0;  // (its rows are padded by 16 bytes: the accumulator layout's stores spread over the banks)
+  struct StreamTables {
+    int pos[kWavesPerBlock][kWin];
+    int pref[kWavesPerBlock][64];
+    int start[kWavesPerBlock][64];
+  };
+  typedef float WaveStates[kWavesPerBlock][NQ][D + kAccPad];
+  struct Apart {
+    StreamTables st;
+    WaveStates acc;
+  };
+  union Overlaid {
+    StreamTables st;
+    WaveStates acc;
+  };
+  __shared__ __attribute__((aligned(16))) std::conditional_t<NQ == 16, Overlaid, Apart> s_u;
+  auto& s_pos = s_u.st.pos;
+  auto& s_pref = s_u.st.pref;
+  auto& s_start = s_u.st.start;
+  auto& s_acc = s_u.acc;
+  __shared__ u32x4 s_new[NQ == 1 ? kWavesPerBlock : 1][2][LPR];  // append variant: the new K / V row, parked until its owner needs it
   __shared__ float s_ml[kWavesPerBlock][NQ][2];
-  __shared__ float s_gm[kWavesPerBlock][NQ], s_gl[kWavesPerBlock][NQ];
+  constexpr int kSliceGroups = NQ == 16 ? 1 : kThreads / D;  // thread groups of the slice merge, see step 5
+  __shared__ float s_gm[kSliceGroups][NQ], s_gl[kSliceGroups][NQ];
+  // sixteen-query pass: q in rows of 256 + 16 bytes (operand reads spread over the banks), the waves' merge weights
+  constexpr int kQRow = 272;
+  __shared__ __attribute__((aligned(16))) unsigned char s_q[NQ == 16 ? 16 * kQRow : 16];
+  __shared__ float s_wgt[NQ == 16 ? kWavesPerBlock : 1][16], s_M[16], s_L[16];
   __shared__ int s_ticket;
 #ifdef SPAN_STAGE_LDS
   __shared__ u32x4 s_stage[kWavesPerBlock][2][U][64];  // measurement build: U K tiles and U V tiles of 1 KiB per wave
@@ -368,13 +445,32 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   auto qrow = [&](int j) { return ((size_t)b * a.q_len + (size_t)(a.q_first + min(j, nq_here - 1))) * a.heads + h; };
   // q pieces of this lane.  Scores carry the factor scale*log2(e), so that exp() becomes exp2(): fp32 q is
   // multiplied by it here, 16-bit q stays as stored and the finished dot product is multiplied instead.
-  typename Elt::Q qv[NQ];
+  constexpr int kVq = NQ == 16 ? 1 : NQ;  // (the sixteen-query pass keeps q in the matrix operand layout instead)
+  typename Elt::Q qv[kVq];
+  if constexpr (NQ < 16) {
 #pragma unroll
-  for (int j = 0; j < NQ; ++j) {
-    const u32x4 qr = *reinterpret_cast<const u32x4*>((const char*)a.q + qrow(j) * ROWB + (uint32_t)lir * 16u);
-    qv[j] = Elt::make_q(qr, a.scale_log2e);
+    for (int j = 0; j < NQ; ++j) {
+      const u32x4 qr = *reinterpret_cast<const u32x4*>((const char*)a.q + qrow(j) * ROWB + (uint32_t)lir * 16u);
+      qv[j] = Elt::make_q(qr, a.scale_log2e);
+    }
   }
   const float post = Elt::kPostScale ? a.scale_log2e : 1.f;
+  // Sixteen-query pass.  Lane (qi, c4) = (lane % 16, lane / 16).  One 16x16x16 MFMA contracts over 16 values k,
+  // lane (i, c) supplying k = 4c .. 4c+3 of row i of A and of column i of B, and leaves C[4c + t][i] in lane (i, c).
+  //  * scores: A = K tile (16 rows), B = Q^T, contraction over the head dimension, 8 MFMAs.  Any fixed assignment
+  //    of the 128 dimensions to (MFMA, c, t) serves as long as K and q use the same: lane (i, c) holds bytes
+  //    16 (4 mm + c) .. + 16 of its row, mm = 0..3, and each 16-byte piece feeds two MFMAs.  Lane (qi, c4) ends up
+  //    with the scores of query qi against rows 4 c4 + t of the tile -
+  //  * outputs: - which is the B operand (P^T) of O^T = V^T P^T, contraction over the tile's rows.  For A = V^T lane
+  //    (i, c) needs V[4c + t][d_i]: it loads the 16-byte piece i of rows 4c + t (whole rows per quarter wave) and
+  //    MFMA e = 0..7 takes element e of the four pieces, so d_i = 8 i + e and lane (qi, c4) accumulates
+  //    O[qi][32 c4 + 8 t + e].  The rescaling factor of query qi is then a per-lane scalar.
+  // q is the same for the four waves and stays in LDS (16 registers fewer per lane): thread tid fetches piece
+  // tid % 16 of query row tid / 16 here and parks it once the span metadata is on its way.
+  const int qi = lane & 15, c4 = lane >> 4;
+  u32x4 q_piece = {0u, 0u, 0u, 0u};
+  if constexpr (NQ == 16)
+    q_piece = *reinterpret_cast<const u32x4*>((const char*)a.q + qrow(tid >> 4) * ROWB + 16u * (uint32_t)(tid & 15));
   // Causal limit (few-query variant): query token j sees no position after its own, q_pos[b] + q_first + j.
   int lim[NQ];
 #pragma unroll
@@ -421,10 +517,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   }
   SPAN_STAMP_AFTER(1, "s", cnt);
 
-  // State of this slice for output column tid (tid < D), per query token: un-normalised, m in log2 units.
-  float M[NQ], L[NQ], o[NQ];
+  // State of this slice once its waves are merged, un-normalised, m in log2 units: a thread that `owns` holds
+  // output column t of query tokens jb .. jb + JT - 1.  Up to four tokens: all of them, in the first D threads;
+  // sixteen: eight per thread, the two halves of the workgroup taking eight tokens each.
+  constexpr int JT = NQ == 16 ? 8 : NQ;
+  const int t = tid % D;
+  const int jb = NQ == 16 ? (tid / D) * JT : 0;
+  const bool owns = NQ == 16 ? true : tid < D;
+  static_assert(NQ < 16 || kThreads == 2 * D, "sixteen tokens: two halves of D threads");
+  float M[JT], L[JT], o[JT];
 #pragma unroll
-  for (int j = 0; j < NQ; ++j) {
+  for (int j = 0; j < JT; ++j) {
     M[j] = -INFINITY;
     L[j] = 0.f;
     o[j] = 0.f;
@@ -479,19 +582,104 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   const __amdgpu_buffer_rsrc_t vslab = slab_resource((const char*)a.v + bh * (size_t)slab_bytes, slab_bytes);
   const uint32_t lane_off = (uint32_t)lir * 16u;
 
-  float m[NQ], l[NQ];
-  float acc[NQ][EPL];
+  float m[kVq], l[kVq];
+  float acc[kVq][EPL];
 #pragma unroll
-  for (int j = 0; j < NQ; ++j) {
+  for (int j = 0; j < kVq; ++j) {
     m[j] = -INFINITY;
     l[j] = 0.f;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) acc[j][i] = 0.f;
   }
+  // Sixteen-query pass: state of query qi in lane (qi, c4).  ref is the reference exponent of the weights (the
+  // running maximum minus 8, the same in the four lanes of a query), lsum this lane's share of their sum,
+  // O[e][t] the un-normalised output column 32 c4 + 8 t + e.
+  float ref = -INFINITY, lsum = 0.f;
+  f32x4 O[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) O[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // Takes one tile of 16 rows into the state.  kr: this lane's four 16-byte pieces of K row qi of the tile; vr:
+  // piece qi of V rows 4 c4 + t; vis[t]: query qi sees row 4 c4 + t (hidden pairs get weight zero, whatever K holds).
+  // per_query (wave-uniform) with row_pos[t], the cache position of row 4 c4 + t: see the second product below.
+  auto absorb = [&](const u32x4* kr, const u32x4* vr, const bool* vis, bool per_query, const int* row_pos) {
+    if constexpr (NQ == 16) {
+      f32x4 sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int mm = 0; mm < 4; ++mm) {
+        const u32x4 qm = *reinterpret_cast<const u32x4*>(&s_q[qi * kQRow + 16 * (4 * mm + c4)]);
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const uint32_t k0 = kr[mm][2 * hh], k1 = kr[mm][2 * hh + 1], q0 = qm[2 * hh], q1 = qm[2 * hh + 1];
+          sc = Elt::mfma(u32x2{k0, k1}, u32x2{q0, q1}, sc);
+        }
+      }
+      float w[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const float d = sc[t];
+        w[t] = vis[t] ? d * post : -INFINITY;
+      }
+      float mx = fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3]));
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      // The weights go into the second product in the storage type, as a rounded value plus the rounded remainder.
+      // With the reference 8 below the maximum they reach 2^8, which keeps the tail of a peaked distribution
+      // (weights below 2^-14 of the largest) out of fp16's subnormal range.
+      const float ref_new = fmaxf(ref, mx - 8.f);
+      const float ref_safe = (ref_new == -INFINITY) ? 0.f : ref_new;
+      const float alpha = __builtin_amdgcn_exp2f(ref - ref_safe);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) w[t] = __builtin_amdgcn_exp2f(w[t] - ref_safe);
+      lsum = fmaf(lsum, alpha, (w[0] + w[1]) + (w[2] + w[3]));
+      ref = ref_new;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {  // (the maximum settles after the first tiles)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) O[e] *= alpha;
+      }
+      u32x2 hi, lo;
+      Elt::split(w, hi, lo);
+      // element e of the four V pieces, as the 16-bit quadruple (rows 4 c4 .. 4 c4 + 3) the MFMA wants
+      auto v_operand = [&](int e) {
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        const uint32_t v0 = vr[0][e >> 1], v1 = vr[1][e >> 1], v2 = vr[2][e >> 1], v3 = vr[3][e >> 1];
+        return u32x2{__builtin_amdgcn_perm(v1, v0, sel), __builtin_amdgcn_perm(v3, v2, sel)};
+      };
+      if (!per_query) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const u32x2 va = v_operand(e);
+          O[e] = Elt::mfma(va, hi, O[e]);
+          O[e] = Elt::mfma(va, lo, O[e]);
+        }
+      } else {
+        // Some V row of the tile is not finite and some query of the pass does not see it: weight zero would not
+        // keep it out of that query's sums (0 * Inf), so the product is taken once per query, with the rows that
+        // query does not see cleared from the V operand, and only that query's column of the result is kept.
+#pragma unroll 1
+        for (int qq = 0; qq < 16; ++qq) {
+          const int last = lim[0] + qq;  // (this branch is only taken under a causal limit: no overflow)
+          const uint32_t keep0 = (row_pos[0] <= last ? 0xffffu : 0u) | (row_pos[1] <= last ? 0xffff0000u : 0u);
+          const uint32_t keep1 = (row_pos[2] <= last ? 0xffffu : 0u) | (row_pos[3] <= last ? 0xffff0000u : 0u);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            u32x2 va = v_operand(e);
+            va = u32x2{va[0] & keep0, va[1] & keep1};
+            f32x4 part = Elt::mfma(va, hi, f32x4{0.f, 0.f, 0.f, 0.f});
+            part = Elt::mfma(va, lo, part);
+            if (qi == qq) O[e] += part;
+          }
+        }
+      }
+    }
+  };
 
   if (NQ == 1 && a.append_pos && lane < LPR) {  // park the new row in LDS (frees the registers)
     s_new[wave][0][lane] = kn_raw;
     s_new[wave][1][lane] = vn_raw;
+  }
+  if constexpr (NQ == 16) {
+    *reinterpret_cast<u32x4*>(&s_q[(tid >> 4) * kQRow + 16 * (tid & 15)]) = q_piece;
+    __syncthreads();
   }
 
   // ---- step 2: virtual token -> KV position for a window's rows (span path only) -----------------
@@ -607,7 +795,105 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     }
   }
 
-  // Few-query pass: the span rows between the first and the last token's causal limit (at most NQ - 1
+  if constexpr (NQ == 16) {
+    // ---- step 3 of the sixteen-query pass ----------------------------------------------------------
+    // Every span row that some real token of the pass sees goes through the tiles, masked per (query, row): rows up
+    // to `last_all` are seen by all tokens, the few after it (the pass's own positions) by the later tokens only.
+    // In the append form those rows are not in the cache yet for this launch: row i of the pass, at position
+    // lim[0] + i, is fetched from k_new / v_new instead (a lane takes each of its rows from one source or the other).
+    const bool limited = a.q_pos != nullptr;
+    const int lim0 = limited ? lim[0] : 0x7fffffff;
+    const int last_all = limited ? lim0 - (append_many ? 1 : 0) : 0x7fffffff;
+    const int last_any = limited ? lim0 + nq_here - 1 : 0x7fffffff;
+    constexpr uint32_t kNoRow = 0xffffff00u;  // an offset past every slab (and still so with a piece offset added)
+    const size_t new_first = (((size_t)b * a.q_len + (size_t)a.q_first) * a.heads + h) * ROWB;
+    const uint32_t new_stride = (uint32_t)a.heads * ROWB;
+    const uint32_t new_bytes = (uint32_t)(nq_here - 1) * new_stride + ROWB;
+    const __amdgpu_buffer_rsrc_t knew = append_many ? slab_resource((const char*)a.k_new + new_first, new_bytes) : kslab;
+    const __amdgpu_buffer_rsrc_t vnew = append_many ? slab_resource((const char*)a.v_new + new_first, new_bytes) : vslab;
+    for (int base = 0; base < wn; base += 16 * U) {
+      u32x4 kr[U][4], vr[U][4];
+      uint32_t okmask[U];  // bit i: row i of the tile takes part
+      bool mixed[U];       // the tile holds rows that only some tokens of the pass see (wave-uniform)
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int live = wn - (base + 16 * u);          // rows of this tile that exist (may be <= 0)
+        const int tb = min(base + 16 * u, kWin - 16);   // (a tile past the window reads table entries it does not use)
+        const int pk = s_pos[wave][tb + qi];
+        const bool okk = qi < live && pk <= last_any;
+        okmask[u] = (uint32_t)__builtin_amdgcn_ballot_w64(okk);
+        mixed[u] = __builtin_amdgcn_ballot_w64(okk && pk > last_all) != 0;
+        if (!(mixed[u] && append_many)) {  // all rows come from the cache: no choice per lane
+          const uint32_t koff = okk ? (uint32_t)pk * ROWB + 16u * (uint32_t)c4 : kNoRow;
+#pragma unroll
+          for (int mm = 0; mm < 4; ++mm) kr[u][mm] = load_row_piece(kslab, koff + 64u * mm);
+          const i32x4 pv4 = *reinterpret_cast<const i32x4*>(&s_pos[wave][tb + 4 * c4]);  // positions of rows 4 c4 .. + 3
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const int pv = pv4[t];
+            const bool okv = (okmask[u] >> (4 * c4 + t)) & 1u;
+            vr[u][t] = load_row_piece(vslab, okv ? (uint32_t)pv * ROWB + 16u * (uint32_t)qi : kNoRow);
+          }
+        } else {
+          if (okk && pk >= lim0) {
+            const uint32_t koff = (uint32_t)(pk - lim0) * new_stride + 16u * (uint32_t)c4;
+#pragma unroll
+            for (int mm = 0; mm < 4; ++mm) kr[u][mm] = __builtin_amdgcn_raw_buffer_load_b128(knew, koff + 64u * mm, 0, 0);
+          } else {
+            const uint32_t koff = okk ? (uint32_t)pk * ROWB + 16u * (uint32_t)c4 : kNoRow;
+#pragma unroll
+            for (int mm = 0; mm < 4; ++mm) kr[u][mm] = load_row_piece(kslab, koff + 64u * mm);
+          }
+          const i32x4 pv4 = *reinterpret_cast<const i32x4*>(&s_pos[wave][tb + 4 * c4]);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const int pv = pv4[t];
+            const bool okv = (okmask[u] >> (4 * c4 + t)) & 1u;
+            if (okv && pv >= lim0)
+              vr[u][t] = __builtin_amdgcn_raw_buffer_load_b128(vnew, (uint32_t)(pv - lim0) * new_stride + 16u * (uint32_t)qi, 0, 0);
+            else
+              vr[u][t] = load_row_piece(vslab, okv ? (uint32_t)pv * ROWB + 16u * (uint32_t)qi : kNoRow);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (base + 16 * u < wn) {
+          const int tb = min(base + 16 * u, kWin - 16);
+          bool vis[4];
+          int row_pos[4];
+          const i32x4 pv4 = *reinterpret_cast<const i32x4*>(&s_pos[wave][tb + 4 * c4]);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const bool okv = (okmask[u] >> (4 * c4 + t)) & 1u;
+            const int pv = pv4[t];
+            row_pos[t] = okv ? pv : 0x7fffffff;
+            vis[t] = okv && row_pos[t] - lim0 <= qi;  // (no limit: lim0 is the largest int and the difference negative)
+          }
+          bool wild = false;  // a V value that is not finite, in a tile with rows hidden from some tokens
+          if (mixed[u]) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const uint32_t w = vr[u][t][i];
+                wild = wild || (w & Elt::kExponent) == Elt::kExponent || (w & (Elt::kExponent << 16)) == (Elt::kExponent << 16);
+              }
+            }
+            wild = __builtin_amdgcn_ballot_w64(wild) != 0;
+          }
+          absorb(kr[u], vr[u], vis, wild, row_pos);
+        }
+      }
+#ifdef SPAN_PHASE_TRACE
+      if (w0 == 0 && base == 0) SPAN_STAMP_AFTER(3, "v", lsum);
+#endif
+      // Compiler barrier: without it the scheduler moves work of the next iteration (and of the merge phase) up into
+      // this one, the 128 registers of four waves per SIMD no longer suffice, and the spill reloads land in this loop.
+      asm volatile("" ::"v"(lsum) : "memory");
+    }
+  } else {
+  // Passes of two or four tokens: the span rows between the first and the last token's causal limit (at most NQ - 1
   // positions of a sequence) are seen by the later tokens only.  The streaming loop below serves the rows every
   // token of the pass sees; these few are taken in here, one at a time, each into the states of exactly the
   // tokens that see it - a hidden row never meets a token's sums, not even with weight zero (0 * Inf).
@@ -726,10 +1012,53 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     if (w0 == 0 && base == 0) SPAN_STAMP_AFTER(3, "v", acc[0][0]);
 #endif
   }
+  }  // fewer than sixteen queries
   }  // windows
-  SPAN_STAMP_AFTER(4, "v", acc[0][0]);
+  SPAN_STAMP_AFTER(4, "v", acc[0][0] + lsum);
 
   // ---- step 4: merge row groups (shuffles), then waves (LDS) ------------------------------------
+  if constexpr (NQ == 16) {
+    // the four lanes of a query hold the weights of disjoint rows and disjoint output columns
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    __syncthreads();  // every wave is done with the streaming tables: the states may overwrite them
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      float* dst = &s_acc[wave][qi][32 * c4 + 8 * tt];
+      *reinterpret_cast<f32x4*>(dst) = f32x4{O[0][tt], O[1][tt], O[2][tt], O[3][tt]};
+      *reinterpret_cast<f32x4*>(dst + 4) = f32x4{O[4][tt], O[5][tt], O[6][tt], O[7][tt]};
+    }
+    if (c4 == 0) {
+      s_ml[wave][qi][0] = ref;
+      s_ml[wave][qi][1] = lsum;
+    }
+    __syncthreads();
+    // the weight of wave w's state in query j's merged state is the same for all columns: 64 threads work them out
+    if (tid < 64) {
+      const int w = tid >> 4, j = tid & 15;
+      const float mw = s_ml[w][j][0], lw = s_ml[w][j][1];
+      float mx = lw > 0.f ? mw : -INFINITY;
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float wgt = lw > 0.f ? __builtin_amdgcn_exp2f(mw - mx) : 0.f;
+      float lj = wgt * lw;
+      lj += __shfl_xor(lj, 16, 64);
+      lj += __shfl_xor(lj, 32, 64);
+      s_wgt[w][j] = wgt;
+      if (w == 0) {
+        s_M[j] = mx;
+        s_L[j] = lj;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < JT; ++j) {
+      M[j] = s_M[jb + j];
+      L[j] = s_L[jb + j];
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w) o[j] = fmaf(s_wgt[w][jb + j], s_acc[w][jb + j][t], o[j]);
+    }
+  } else {
 #pragma unroll
   for (int j = 0; j < NQ; ++j) {
 #pragma unroll
@@ -764,15 +1093,26 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
       }
     }
   }
+  }  // up to four tokens
   }  // cnt > 0
   SPAN_STAMP_AFTER(5, "v", o[0]);
 
-  if (nsl == 1) {  // one slice for this (batch, head): this workgroup owns the output row
-    if (tid < D) {
+  // Output column t of an un-normalised state.  (The sixteen-token pass multiplies by the reciprocal of the
+  // sum, one division per token instead of one per element.)
+  auto store_rows = [&](const float* ll, const float* oo) {
 #pragma unroll
-      for (int j = 0; j < NQ; ++j)
-        if (j < nq_here) a.out[qrow(j) * D + tid] = L[j] > 0.f ? o[j] / L[j] : 0.f;
+    for (int j = 0; j < JT; ++j) {
+      if (jb + j < nq_here) {
+        float r;
+        if constexpr (NQ == 16) r = ll[j] > 0.f ? oo[j] * (1.f / ll[j]) : 0.f;
+        else r = ll[j] > 0.f ? oo[j] / ll[j] : 0.f;
+        a.out[qrow(jb + j) * D + t] = r;
+      }
     }
+  };
+
+  if (nsl == 1) {  // one slice for this (batch, head): this workgroup owns the output row
+    if (owns) store_rows(L, o);
     SPAN_STAMP_ACKED(6);
     SPAN_TRACE_FLUSH();
     return;
@@ -789,13 +1129,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
   // state of slice s of (b, h) lives in slot (y0 + s) * heads + h
   const size_t H = (size_t)a.heads;
   const size_t my_slot = (size_t)(y0 + split) * H + h;
-  if (tid < D) {
+  if (owns) {
 #pragma unroll
-    for (int j = 0; j < NQ; ++j) {
-      if (cnt > 0) publish(&a.part_acc[(my_slot * NQ + j) * D + tid], o[j]);
-      if (tid == 0) {
-        publish(&a.part_ml[(my_slot * NQ + j) * 2], M[j]);
-        publish(&a.part_ml[(my_slot * NQ + j) * 2 + 1], L[j]);
+    for (int j = 0; j < JT; ++j) {
+      if (jb + j >= nq_here) continue;  // (a padded pass: tokens that do not exist leave no state)
+      if (cnt > 0) publish(&a.part_acc[(my_slot * NQ + jb + j) * D + t], o[j]);
+      if (t == 0) {
+        publish(&a.part_ml[(my_slot * NQ + jb + j) * 2], M[j]);
+        publish(&a.part_ml[(my_slot * NQ + jb + j) * 2 + 1], L[j]);
       }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my published stores are acknowledged
@@ -810,36 +1151,43 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
     return;
   }
 
-  constexpr int G = kThreads / D;  // column t is merged by G threads, each over every G-th slice
-  const int g = tid / D, t = tid % D;
+  // Column t of tokens jb .. is merged by G threads, each over every G-th slice (sixteen tokens: G = 1, the two
+  // halves of the workgroup already split the tokens).
+  constexpr int G = kSliceGroups;
+  const int g = NQ == 16 ? 0 : tid / D;
   const size_t slot0 = (size_t)y0 * H + h;  // slice s of this (b, h) is slot0 + s * H
-  float mm[NQ], ll[NQ], oo[NQ];
+  float mm[JT], ll[JT], oo[JT];
 #pragma unroll
-  for (int j = 0; j < NQ; ++j) {
+  for (int j = 0; j < JT; ++j) {
     mm[j] = -INFINITY;
     ll[j] = 0.f;
     oo[j] = 0.f;
   }
   // The states are fetched a batch at a time, all loads of a batch in flight together (one trip to memory for up
   // to kBatch * G slices), and merged in slice order.
-  constexpr int kBatch = NQ == 1 ? 8 : (NQ == 2 ? 4 : 2);
+  constexpr int kBatch = NQ == 1 ? 8 : (NQ == 2 ? 4 : (NQ == 4 ? 2 : 1));
   for (int s0 = g; s0 < nsl; s0 += G * kBatch) {
-    float ms[kBatch][NQ], ls[kBatch][NQ], as[kBatch][NQ];
+    float ms[kBatch][JT], ls[kBatch][JT], as[kBatch][JT];
 #pragma unroll
     for (int k = 0; k < kBatch; ++k) {
       const size_t slot = slot0 + (size_t)min(s0 + k * G, nsl - 1) * H;  // (past the end: a slot that exists, unused)
 #pragma unroll
-      for (int j = 0; j < NQ; ++j) {
-        ms[k][j] = observe(&a.part_ml[(slot * NQ + j) * 2]);
-        ls[k][j] = observe(&a.part_ml[(slot * NQ + j) * 2 + 1]);
-        as[k][j] = observe(&a.part_acc[(slot * NQ + j) * D + t]);
+      for (int j = 0; j < JT; ++j) {
+        if (jb + j < nq_here) {
+          ms[k][j] = observe(&a.part_ml[(slot * NQ + jb + j) * 2]);
+          ls[k][j] = observe(&a.part_ml[(slot * NQ + jb + j) * 2 + 1]);
+          as[k][j] = observe(&a.part_acc[(slot * NQ + jb + j) * D + t]);
+        } else {
+          ms[k][j] = -INFINITY;
+          ls[k][j] = as[k][j] = 0.f;
+        }
       }
     }
 #pragma unroll
     for (int k = 0; k < kBatch; ++k) {
       if (s0 + k * G < nsl) {
 #pragma unroll
-        for (int j = 0; j < NQ; ++j) {
+        for (int j = 0; j < JT; ++j) {
           const bool full = ls[k][j] > 0.f;  // slot of an empty slice is never written: select, do not scale
           const float av = full ? as[k][j] : 0.f;
           merge_state(mm[j], ll[j], &oo[j], 1, full ? ms[k][j] : -INFINITY, full ? ls[k][j] : 0.f, &av);
@@ -847,27 +1195,31 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 
       }
     }
   }
-  if (g > 0) {
+  if constexpr (G > 1) {
+    if (g > 0) {
 #pragma unroll
-    for (int j = 0; j < NQ; ++j) {
-      s_acc[g][j][t] = oo[j];
-      if (t == 0) {
-        s_gm[g][j] = mm[j];
-        s_gl[g][j] = ll[j];
+      for (int j = 0; j < JT; ++j) {
+        s_acc[g][j][t] = oo[j];
+        if (t == 0) {
+          s_gm[g][j] = mm[j];
+          s_gl[g][j] = ll[j];
+        }
       }
     }
+    __syncthreads();
   }
-  __syncthreads();
   if (g == 0) {
+    if constexpr (G > 1) {
 #pragma unroll
-    for (int j = 0; j < NQ; ++j) {
+      for (int j = 0; j < JT; ++j) {
 #pragma unroll
-      for (int k = 1; k < G; ++k) {
-        const float o2 = s_acc[k][j][t];
-        merge_state(mm[j], ll[j], &oo[j], 1, s_gm[k][j], s_gl[k][j], &o2);
+        for (int k = 1; k < G; ++k) {
+          const float o2 = s_acc[k][j][t];
+          merge_state(mm[j], ll[j], &oo[j], 1, s_gm[k][j], s_gl[k][j], &o2);
+        }
       }
-      if (j < nq_here) a.out[qrow(j) * D + t] = ll[j] > 0.f ? oo[j] / ll[j] : 0.f;
     }
+    store_rows(ll, oo);
     // leave the ticket counter ready for the next call (same device-coherent access path as the tickets)
     if (tid == 0) __hip_atomic_store(&a.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
@@ -953,7 +1305,7 @@ int launch_typed(const LaunchArgsTable& a, const RunTables* runs, GridMode mode,
 #ifdef SPAN_IN_FLIGHT
   constexpr int kInFlight = SPAN_IN_FLIGHT;
 #else
-  constexpr int kInFlight = (kRowsPerLoad >= 8 ? 2 : 4) / (NQ > 1 ? 2 : 1);
+  constexpr int kInFlight = NQ == 16 ? SPAN_MQ_TILES /* tiles of 16 rows */ : (kRowsPerLoad >= 8 ? 2 : 4) / (NQ > 1 ? 2 : 1);
 #endif
   if (mode == GridMode::kRuns) {
     if constexpr (!kDense) {
@@ -988,6 +1340,10 @@ int launch_queries(const LaunchArgsTable& a, const RunTables* runs, int nq, Grid
   if constexpr (!kDense) {  // the few-query variant exists for the span form only
     if (nq == 2) return launch_typed<Elt, D, false, 2>(a, runs, mode, batch, stream);
     if (nq == 4) return launch_typed<Elt, D, false, 4>(a, runs, mode, batch, stream);
+    if constexpr (Elt::kHasMfma && D == 128) {
+      if (nq == 16) return launch_typed<Elt, D, false, 16>(a, runs, mode, batch, stream);
+    }
+    if (nq != 1) return SPAN_ERR_SHAPE;  // (not reachable: the planner asks only for passes that exist)
   }
   return launch_typed<Elt, D, kDense, 1>(a, runs, mode, batch, stream);
 }

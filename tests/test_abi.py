@@ -145,21 +145,34 @@ def test_partition_arithmetic_exact():
 
 
 def test_partition_follows_the_query_token_count():
-    """One resident round is 2048 workgroups for one query token, 1536 for two, 1024 for three or more, and a
-    ragged batch of 30 sequences (two slices per sequence wanted) is capped by it; the workspace grows with the
-    tokens one pass serves (1, 2 or 4), never with q_len itself."""
+    """One resident round is 2048 workgroups for one query token, 1536 for two, 1024 for the four-token pass and for
+    the sixteen-token pass (16-bit types with head_dim 128, from three tokens on), and a ragged batch of 30
+    sequences (two slices per sequence wanted) is capped by it; the workspace grows with the tokens one pass serves
+    (1, 2, 4 or 16), never with q_len itself."""
     tok = np.linspace(1500, 4096, 30).astype(np.int64)
-    plans = {}
-    for q_len in (0, 1, 2, 3, 4, 8, 64):
-        d = binding.make_desc(30, 32, 128, 4096, 1, 10, 4096, 0, tokens_per_seq=tok, q_len=q_len)
-        plans[q_len] = span.span_plan_query(d)
+    plans, plans32 = {}, {}
+    for q_len in (0, 1, 2, 3, 4, 5, 8, 64):
+        plans[q_len] = span.span_plan_query(binding.make_desc(30, 32, 128, 4096, 1, 10, 4096, 0, tokens_per_seq=tok, q_len=q_len))
+        plans32[q_len] = span.span_plan_query(binding.make_desc(30, 32, 128, 4096, 0, 10, 4096, 0, tokens_per_seq=tok, q_len=q_len))
     assert plans[0] == plans[1]
+    assert [plans[q]["queries_per_pass"] for q in (1, 2, 3, 4, 5, 64)] == [1, 2, 16, 16, 16, 16]
+    assert [plans32[q]["queries_per_pass"] for q in (1, 2, 3, 4, 5, 64)] == [1, 2, 4, 4, 4, 4]    # fp32: vector units only
     assert 1536 < plans[1]["workgroups"] <= 1920           # 2 x 30 slices per head wanted, 64 would fit
-    assert 1024 < plans[2]["workgroups"] <= 1536 and 768 < plans[4]["workgroups"] <= 1024
-    assert plans[3] == plans[4] == plans[8] == plans[64]
+    assert 1024 < plans[2]["workgroups"] <= 1536 and 768 < plans32[4]["workgroups"] <= 1024
+    assert 960 <= plans[8]["workgroups"] <= 1024           # 30 x 32 pairs nearly fill the round by themselves
+    assert plans[3] == plans[4] == plans[5] == plans[8] == plans[64]
+    assert plans32[3] == plans32[4] == plans32[8] == plans32[64]
     per_slot = lambda pl: (pl["workspace_bytes"] - 3840) / pl["workgroups"]      # 3840 B of counters at this size
     assert abs(per_slot(plans[1]) - 130 * 4) < 2 and abs(per_slot(plans[2]) - 2 * 130 * 4) < 2
-    assert abs(per_slot(plans[4]) - 4 * 130 * 4) < 2
+    assert abs(per_slot(plans32[4]) - 4 * 130 * 4) < 2 and abs(per_slot(plans[8]) - 16 * 130 * 4) < 2
+    few = np.linspace(1500, 4096, 6).astype(np.int64)
+    sliced = span.span_plan_query(binding.make_desc(6, 32, 128, 4096, 1, 10, 4096, 0, tokens_per_seq=few, q_len=8))
+    assert 192 < sliced["workgroups"] <= 1024 and sliced["max_splits"] > 1
+    counters = 6 * 32 * 4
+    assert abs((sliced["workspace_bytes"] - counters) / sliced["workgroups"] - 16 * 130 * 4) < 8
+    # head_dim 64 has no sixteen-token pass either
+    d8 = binding.make_desc(30, 32, 64, 4096, 1, 10, 4096, 0, tokens_per_seq=tok, q_len=8)
+    assert span.span_plan_query(d8)["queries_per_pass"] == 4
     for bad in (-1, 65):
         d = binding.make_desc(8, 32, 128, 4096, 1, 10, 4096, 0, q_len=bad)
         with pytest.raises(span.SpanAttnError):

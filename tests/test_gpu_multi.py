@@ -47,7 +47,7 @@ def new_tokens_at_the_end(sp, q_len):
 
 
 @pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
-@pytest.mark.parametrize("q_len", [2, 4])
+@pytest.mark.parametrize("q_len", [2, 4, 16])
 def test_workload_multi_parity(cid, q_len, gpu_device):
     """The five workloads: every span ends with the recent-token interval, so the new tokens are inside it."""
     cfg = CONFIGS[cid]
@@ -63,7 +63,7 @@ def test_workload_multi_parity(cid, q_len, gpu_device):
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("D", [64, 128])
-@pytest.mark.parametrize("q_len", [1, 2, 3, 4, 5, 8])
+@pytest.mark.parametrize("q_len", [1, 2, 3, 4, 5, 8, 13, 16, 17, 40])
 def test_multi_all_kernel_instances(dtype, D, q_len, gpu_device):
     """Every (type, head_dim) instance, token counts that pad a pass (3), fill it (2, 4) and need several (5, 8);
     ragged sequences, forced slicing so that the cross-workgroup merge runs per query token."""
@@ -159,7 +159,7 @@ def test_multi_random_shapes_and_lists(seed, gpu_device):
     D = [128, 64][(seed // 3) % 2]
     B, H = int(rng.integers(1, 6)), int(rng.choice([1, 3, 8, 32]))
     L = int(rng.choice([40, 300, 1500, 5000]))
-    q_len = int(rng.integers(1, 10))
+    q_len = int(rng.integers(1, 10)) if seed % 3 else int(rng.integers(10, 36))
     cfg = DecodeConfig(300 + seed, "random-multi", B, H, D, L, L, dtype, TOL[dtype])
     ctx = rng.integers(q_len + 1, L + 1, size=B).astype(np.int32)
     per_seq = []
@@ -191,7 +191,7 @@ def _poison(K, V, b, rows, gpu_device):
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("D", [64, 128])
-@pytest.mark.parametrize("q_len", [1, 2, 3, 4, 6])
+@pytest.mark.parametrize("q_len", [1, 2, 3, 4, 6, 11, 16, 21])
 def test_poisoned_span_rows_past_the_limits_have_no_influence(dtype, D, q_len, gpu_device):
     """GPU twin of the oracle pin of the same name (masked positions have no influence, Sec. 2.2 mask paragraph).
     Span rows after the last query token's causal limit hold NaN (K) and +-Inf (V), as an uninitialised
@@ -228,7 +228,7 @@ def test_poisoned_span_rows_past_the_limits_have_no_influence(dtype, D, q_len, g
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
-@pytest.mark.parametrize("q_len", [2, 4, 7])
+@pytest.mark.parametrize("q_len", [2, 4, 7, 16, 19])
 def test_a_row_only_later_tokens_see_does_not_touch_the_earlier_ones(dtype, q_len, gpu_device):
     """The row at the last token's own position holds +Inf in V: the last token's output is not finite (in the
     oracle too), every earlier token's row must equal the oracle's finite result (no 0 * Inf)."""

@@ -68,7 +68,7 @@ def run_case(cfg, sp, pos, q_len, device, seed=0, what="", **kw):
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("D", [64, 128])
-@pytest.mark.parametrize("q_len", [1, 2, 3, 4, 5, 8])
+@pytest.mark.parametrize("q_len", [1, 2, 3, 4, 5, 8, 16, 23])
 def test_every_instance_and_token_count(dtype, D, q_len, gpu_device):
     """The new tokens close the span's last interval; ragged sequences; unsplit and sliced."""
     cfg = DecodeConfig(99, "multi-append", 3, 5, D, 700, 700, dtype, TOL[dtype])
@@ -83,7 +83,7 @@ def test_every_instance_and_token_count(dtype, D, q_len, gpu_device):
 
 
 @pytest.mark.parametrize("cid", [2, 3, 4])
-@pytest.mark.parametrize("q_len", [2, 4])
+@pytest.mark.parametrize("q_len", [2, 4, 16])
 def test_workload_scale(cid, q_len, gpu_device):
     """The workloads' spans end with the recent-token interval: the new tokens are its last q_len positions."""
     cfg = CONFIGS[cid]

@@ -407,10 +407,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(waves_
   // Tables of the streaming phase and the waves' states of the merge phase.  The sixteen-query pass overlays the
   // two (a barrier separates the phases there), which keeps it at four workgroups per CU.
   constexpr int kAccPad = NQ == 16 ? 4 : 0;  // (its rows are padded by 16 bytes: the accumulator layout's stores spread over the banks)
+  constexpr int kQRow = 272;  // sixteen-query pass: q in rows of 256 + 16 bytes (operand reads spread over the banks)
   struct StreamTables {
     int pos[kWavesPerBlock][kWin];
     int pref[kWavesPerBlock][64];
     int start[kWavesPerBlock][64];
+    unsigned char q[NQ == 16 ? 16 * kQRow : 16] __attribute__((aligned(16)));
   };
   typedef float WaveStates[kWavesPerBlock][NQ][D + kAccPad];
   struct Apart {
@@ -430,9 +432,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(waves_
   __shared__ float s_ml[kWavesPerBlock][NQ][2];
   constexpr int kSliceGroups = NQ == 16 ? 1 : kThreads / D;  // thread groups of the slice merge, see step 5
   __shared__ float s_gm[kSliceGroups][NQ], s_gl[kSliceGroups][NQ];
-  // sixteen-query pass: q in rows of 256 + 16 bytes (operand reads spread over the banks), the waves' merge weights
-  constexpr int kQRow = 272;
-  __shared__ __attribute__((aligned(16))) unsigned char s_q[NQ == 16 ? 16 * kQRow : 16];
+  auto& s_q = s_u.st.q;
   __shared__ float s_wgt[NQ == 16 ? kWavesPerBlock : 1][16], s_M[16], s_L[16];
   __shared__ int s_ticket;
 #ifdef SPAN_STAGE_LDS

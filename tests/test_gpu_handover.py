@@ -9,7 +9,7 @@ import torch
 
 import oracle
 import paper_2404_09336_amd as span
-from workloads import CONFIGS, DecodeConfig, SpanBatch, draw_qkv, draw_spans, to_host_raw
+from workloads import CONFIGS, DecodeConfig, SpanBatch, draw_qkv, draw_queries, draw_spans, to_host_raw
 
 pytestmark = pytest.mark.gpu
 
@@ -90,3 +90,42 @@ def test_uniform_grid_with_empty_slices_is_bit_reproducible(gpu_device):
     cfg = CONFIGS[4]
     sp = draw_spans(cfg)
     hammer(cfg, sp, gpu_device, "config 4, uniform grid")
+
+
+@pytest.mark.parametrize("q_len", [2, 5, 16])
+def test_sliced_few_query_calls_are_bit_reproducible(q_len, gpu_device):
+    """The few-query passes hand over one state per query token and slice (two tokens: vector-ALU pass; five and
+    sixteen: the sixteen-token pass, five leaving eleven states of the slot unwritten)."""
+    cfg = CONFIGS[2]
+    sp = draw_spans(cfg)
+    tok = sp.tokens_per_seq()
+    _, K, V = draw_qkv(cfg, sp.ctx_lens, device=gpu_device)
+    q = draw_queries(cfg, q_len, device=gpu_device)
+    lists = [_dev(a, gpu_device) for a in (sp.offsets, sp.starts, sp.ends)]
+    q_pos_host = (sp.ctx_lens - q_len).astype(np.int32)
+    q_pos = _dev(q_pos_host, gpu_device)
+    kw = dict(max_tokens=int(tok.max()), tokens_per_seq=tok)
+    first = span.prepare_span_decode_attn_multi(q, K, V, *lists, q_pos, np.float32(cfg.scale), **kw)
+    plan = span.span_plan_query(first.desc)
+    assert plan["max_splits"] > 1 and plan["queries_per_pass"] == (2 if q_len == 2 else 16), plan
+    workspace = first._keepalive[-1]
+    outs = [torch.empty_like(first.out) for _ in range(RING)]
+    calls = [span.prepare_span_decode_attn_multi(q, K, V, *lists, q_pos, np.float32(cfg.scale), outs[i],
+                                                 workspace=workspace, **kw) for i in range(RING)]
+    want = first().clone()
+    torch.cuda.synchronize()
+    ref = oracle.span_attn_multi(to_host_raw(q), to_host_raw(K), to_host_raw(V), sp.offsets, sp.starts, sp.ends,
+                                 q_pos_host, np.float32(cfg.scale), dtype=cfg.dtype)
+    assert float(np.abs(want.cpu().numpy().astype(np.float64) - ref).max()) <= cfg.tol
+    done = 0
+    while done < CALLS // 4:
+        for _ in range(4):
+            for c in calls:
+                c()
+            done += RING
+        differing = sum(int((o != want).sum()) for o in outs)
+        assert differing == 0, f"{q_len} tokens: {differing} output elements differ from the first call after {done} calls"
+        for o in outs:
+            o.fill_(float("nan"))
+    print(f"[handover] few-query, {q_len} tokens: {done} calls, {plan['max_splits']} slices per pair at most, "
+          f"{plan['workgroups']} workgroups: all outputs bit-identical", flush=True)

@@ -441,7 +441,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(waves_
 
   // Query token j of this launch is row (b, q_first + j, h) of q and out; a launch whose last tokens do
   // not exist (q_len not a multiple of NQ) computes them from the last real one and never writes them.
-  const int nq_here = min(NQ, a.q_len - a.q_first);
+  const int nq_here = NQ == 1 ? 1 : min(NQ, a.q_len - a.q_first);  // (the one-token kernel serves one token, whatever q_len says)
   auto qrow = [&](int j) { return ((size_t)b * a.q_len + (size_t)(a.q_first + min(j, nq_here - 1))) * a.heads + h; };
   // q pieces of this lane.  Scores carry the factor scale*log2(e), so that exp() becomes exp2(): fp32 q is
   // multiplied by it here, 16-bit q stays as stored and the finished dot product is multiplied instead.

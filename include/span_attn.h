@@ -150,8 +150,11 @@ int span_decode_attn_static(const span_attn_desc_t* desc, const void* q, const v
  * through the sequence's one span (a span is chosen once per group of tokens, Sec. 3.2, so the tokens
  * of a group share it).  Among themselves the tokens keep the causal mask of Sec. 2.2: query token j
  * of sequence b attends the span positions p <= q_pos[b] + j and no later one; eqs. (4)-(6) apply to
- * each query row.  Every K / V row of the span is fetched once per pass and serves up to four query
- * tokens; more than four take ceil(q_len / 4) passes.
+ * each query row.  Every K / V row of the span is fetched once per pass over the span and serves all
+ * query tokens of the pass: up to 16 for fp16 / bf16 rows of head_dim 128 (from three tokens on the pass
+ * runs on the matrix cores), up to 4 otherwise; q_len tokens take ceil(q_len / tokens per pass) passes
+ * (span_plan_query reports the tokens per pass).  The weights of the matrix-core pass enter the p.V product
+ * as two 16-bit terms (about 16 mantissa bits for bf16, 22 for fp16); sums and outputs are fp32.
  *   q      : device, desc->dtype, [batch, q_len, heads, head_dim]
  *   q_pos  : device int32 [batch], cache position of query token 0 (its K / V row, like those of the
  *            other new tokens, is already in the cache and inside the span if it is to be attended);

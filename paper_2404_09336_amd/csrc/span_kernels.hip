@@ -309,12 +309,6 @@ __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? l
 // K / V rows are fetched with raw buffer loads: the descriptor covers exactly one (batch, head) slab,
 // so the hardware itself returns zeros for any offset outside it, and the cache policy is explicit.
 // Non-temporal (streaming) loads: every row is used once; measured 17 % faster than default-policy loads.
-#ifndef SPAN_MQ_WAVES
-#define SPAN_MQ_WAVES 4
-#endif
-#ifndef SPAN_MQ_TILES
-#define SPAN_MQ_TILES 1
-#endif
 #ifndef SPAN_ROW_LOAD_POLICY
 #define SPAN_ROW_LOAD_POLICY 2  // (a measurement build overrides it to time the other policies)
 #endif
@@ -353,7 +347,14 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int 
 //
 // NQ = 16 (16-bit types, D = 128) is a dense contraction and runs on the matrix cores: a wave takes its rows in
 // tiles of 16, scores S^T = K Q^T and outputs O^T = V^T P^T are 16x16x16 MFMAs, the running sums stay in the
-// accumulator layout (168 registers, 3 waves per SIMD).
+// accumulator layout.  Four waves per SIMD (128 registers) with one tile in flight per wave measured best: three
+// waves with one or two tiles in flight are 10-14 % slower on batch 64 x ~155 positions.
+#ifndef SPAN_MQ_WAVES
+#define SPAN_MQ_WAVES 4  // (a measurement build overrides these two to time the other shapes)
+#endif
+#ifndef SPAN_MQ_TILES
+#define SPAN_MQ_TILES 1
+#endif
 constexpr int waves_per_simd(int nq) { return nq == 1 ? 8 : (nq == 2 ? 6 : (nq == 4 ? 4 : SPAN_MQ_WAVES)); }
 
 template <class Elt, int D, bool kDense, int U, int NQ, class Args>

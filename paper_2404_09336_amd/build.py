@@ -15,8 +15,6 @@ SOURCES = [os.path.join(CSRC, "span_kernels.hip"), os.path.join(CSRC, "span_host
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         # the kernels' leading pointer arguments arrive in scalar registers at wave start (8 SGPRs = 4 pointers)
-         "-mllvm", "-amdgpu-kernarg-preload-count=8",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 VARIANTS = {
     # thread 0 of every workgroup records a clock value at each phase boundary (bench.py --phase-trace)

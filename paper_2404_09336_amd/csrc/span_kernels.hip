@@ -359,11 +359,7 @@ constexpr int waves_per_simd(int nq) { return nq == 1 ? 8 : (nq == 2 ? 6 : (nq =
 
 template <class Elt, int D, bool kDense, int U, int NQ, class Args>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(waves_per_simd(NQ), waves_per_simd(NQ)))) void decode_kernel(
-    const int32_t* __restrict__ p_offsets, const int32_t* __restrict__ p_starts, const int32_t* __restrict__ p_ends,
-    const int32_t* __restrict__ p_ctx_lens, const Args a) {
-  // The four metadata pointers come first and as arguments of their own: the build asks for them to be preloaded into
-  // scalar registers at wave start, so that the first dependent load of the start-up chain (offsets[b]) does not wait
-  // for a load of the argument block.
+    const Args a) {
   constexpr int EPL = Elt::kPerVec;        // elements per lane (one 128-bit piece)
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPL = 64 / LPR;            // rows per wave-wide load
@@ -491,22 +487,22 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(waves_
   if constexpr (Args::kHasRuns) {
     n_total = 0;  // the slice's rows come from the arguments, see below
   } else if (kDense) {
-    n_total = clampi(p_ctx_lens[b], 0, a.max_len);
+    n_total = clampi(a.ctx_lens[b], 0, a.max_len);
   } else {
-    off0 = clampi(p_offsets[b], 0, a.num_intervals);
-    const int off1 = clampi(p_offsets[b + 1], off0, a.num_intervals);
+    off0 = clampi(a.offsets[b], 0, a.num_intervals);
+    const int off1 = clampi(a.offsets[b + 1], off0, a.num_intervals);
     off0 = __builtin_amdgcn_readfirstlane(off0);
     n_int = __builtin_amdgcn_readfirstlane(off1 - off0);
     SPAN_STAMP_AFTER(10, "s", n_int);
     if (lane < n_int) {
-      st0 = p_starts[off0 + lane];
-      len0 = clampi(p_ends[off0 + lane] - st0, 0, a.max_len);
+      st0 = a.starts[off0 + lane];
+      len0 = clampi(a.ends[off0 + lane] - st0, 0, a.max_len);
     }
     incl0 = wave_inclusive_scan(len0, lane);
     n_total = __builtin_amdgcn_readlane(incl0, 63);
     for (int c0 = 64; c0 < n_int && n_total < scan_stop; c0 += 64) {
       int len = 0;
-      if (c0 + lane < n_int) len = clampi(p_ends[off0 + c0 + lane] - p_starts[off0 + c0 + lane], 0, a.max_len);
+      if (c0 + lane < n_int) len = clampi(a.ends[off0 + c0 + lane] - a.starts[off0 + c0 + lane], 0, a.max_len);
       n_total += __builtin_amdgcn_readlane(wave_inclusive_scan(len, lane), 63);
     }
   }
@@ -702,8 +698,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(waves_
         incl = incl0;
       } else {
         if (c0 + lane < n_int) {
-          st = p_starts[off0 + c0 + lane];
-          len = clampi(p_ends[off0 + c0 + lane] - st, 0, a.max_len);
+          st = a.starts[off0 + c0 + lane];
+          len = clampi(a.ends[off0 + c0 + lane] - st, 0, a.max_len);
         }
         incl = wave_inclusive_scan(len, lane);
       }
@@ -1318,18 +1314,18 @@ int launch_typed(const LaunchArgsTable& a, const RunTables* runs, GridMode mode,
       LaunchArgsRuns ra;
       static_cast<LaunchArgs&>(ra) = static_cast<const LaunchArgs&>(a);
       ra.r = *runs;
-      hipLaunchKernelGGL((decode_kernel<Elt, D, false, kInFlight, NQ, LaunchArgsRuns>), grid, dim3(kThreads), 0, stream, a.offsets, a.starts, a.ends, a.ctx_lens, ra);
+      hipLaunchKernelGGL((decode_kernel<Elt, D, false, kInFlight, NQ, LaunchArgsRuns>), grid, dim3(kThreads), 0, stream, ra);
     } else {
       return SPAN_ERR_SHAPE;  // (not reachable: the dense form never plans runs)
     }
   } else if (mode == GridMode::kTable) {
     const dim3 grid((unsigned)a.heads, (unsigned)a.total_slices, 1u);
-    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsTable>), grid, dim3(kThreads), 0, stream, a.offsets, a.starts, a.ends, a.ctx_lens, a);
+    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsTable>), grid, dim3(kThreads), 0, stream, a);
   } else {
     const dim3 grid((unsigned)a.heads, (unsigned)a.num_splits, (unsigned)batch);
     LaunchArgsPlain plain;
     static_cast<LaunchArgs&>(plain) = static_cast<const LaunchArgs&>(a);
-    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsPlain>), grid, dim3(kThreads), 0, stream, a.offsets, a.starts, a.ends, a.ctx_lens, plain);
+    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsPlain>), grid, dim3(kThreads), 0, stream, plain);
   }
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) {

@@ -252,3 +252,31 @@ def test_a_row_only_later_tokens_see_does_not_touch_the_earlier_ones(dtype, q_le
         got = out.cpu().numpy().astype(np.float64)
         check(got[:, :q_len - 1], ref[:, :q_len - 1], cfg.tol, f"band row, {dtype} q_len={q_len} {sorted(kw)}")
         assert not np.isfinite(got[:, q_len - 1]).any()
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("q_len", [3, 16])
+def test_peaked_scores_with_a_long_light_tail_in_the_matrix_pass(dtype, q_len, gpu_device):
+    """One span row outweighs every other by 2^15 and 2^20, but the other ~5000 rows together still carry 13 % and
+    0.5 % of the sum.  The sixteen-token pass feeds the weights to the matrix cores as 16-bit values: weights that far
+    below the largest must neither vanish (fp16's normal range ends 2^14 below one) nor lose the sum's accuracy.
+    Scores are set exactly through one non-zero query component."""
+    L = 5000
+    cfg = DecodeConfig(95, f"multi-peaked-{dtype}", 2, 2, 128, L, L, dtype, TOL[dtype])
+    ctx = np.full(cfg.batch, L, np.int32)
+    sp = SpanBatch.from_lists([[(0, L)], [(0, 2500), (2600, L)]], ctx)
+    _, K, V = draw_qkv(cfg, ctx, device=gpu_device)
+    q = torch.zeros((cfg.batch, q_len, cfg.heads, cfg.head_dim), dtype=K.dtype, device=gpu_device)
+    q[..., 0] = 16.0
+    per_unit = 16.0 * float(np.float32(cfg.scale))            # score per unit of K[..., 0]
+    K[..., 0] = (-15.0 * np.log(2.0)) / per_unit              # every row: weight 2^-15 of the heavy one
+    K[1, :, :, 0] = (-20.0 * np.log(2.0)) / per_unit          # second sequence: 2^-20
+    K[:, :, 7, 0] = 0.0                                       # the heavy row
+    q_pos = new_tokens_at_the_end(sp, q_len)
+    ref = oracle_multi(cfg, sp, q, K, V, q_pos)
+    heavy = V[:, :, 7].float().cpu().numpy().astype(np.float64)
+    share = np.abs(ref[:, 0] - heavy).max()
+    assert share > 1e-3, "the tail must matter in the reference, or the case proves nothing"
+    for kw in (dict(), dict(num_splits=5, tokens_per_seq=None)):
+        got = run_multi(cfg, sp, q, K, V, q_pos, gpu_device, **kw)
+        check(got, ref, 2e-5, f"peaked {dtype} q_len={q_len} {sorted(kw)}")

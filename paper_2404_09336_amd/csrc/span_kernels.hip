@@ -309,6 +309,28 @@ __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? l
 // K / V rows are fetched with raw buffer loads: the descriptor covers exactly one (batch, head) slab,
 // so the hardware itself returns zeros for any offset outside it, and the cache policy is explicit.
 // Non-temporal (streaming) loads: every row is used once; measured 17 % faster than default-policy loads.
+// A wave sends its first batch of row loads, and consumes it, at raised instruction priority and drops back to the
+// default for the rest of its rows.  Among waves of equal priority a SIMD issues the oldest first, so without this the
+// waves of the workgroups that arrived last on a CU get their first rows only when the earlier ones are nearly done
+// (per-workgroup stamps: first rows after 4 us for the first quarter of a launch, after 15-18 us for the last) and
+// the launch ends on a thin tail of late starters.  Measured on batch 64 x ~155 positions: 27.67 -> 27.11 us; raising
+// the priority for the start-up chain as well, or by progress through the rows, gains less or loses.  One-token
+// kernels for 16-bit rows only, and only launches whose slices hold up to four batches of rows per wave (kBoost
+// instances, chosen by the launcher): the passes that serve several tokens lose by it (3 tokens: 31.9 -> 33.6 us), fp32
+// rows at the same shape (5 batches) lose 1 %, 9 batches (batch 8 x 300..2000) lose 0.5 %, 16 and more gain nothing;
+// even the untaken branch in the loop costs the longer streams 0.5 %, hence instances of their own.
+#ifndef SPAN_FIRST_BATCH_PRIORITY
+#define SPAN_FIRST_BATCH_PRIORITY 3  // (a measurement build sets 0 to time the default arbitration)
+#endif
+constexpr int kBoostUpToBatches = 4;  // per wave
+__device__ __forceinline__ void first_batch_priority(bool first_batch) {
+#if SPAN_FIRST_BATCH_PRIORITY > 0
+  if (first_batch) __builtin_amdgcn_s_setprio(SPAN_FIRST_BATCH_PRIORITY);
+  else __builtin_amdgcn_s_setprio(0);
+#else
+  (void)first_batch;
+#endif
+}
 #ifndef SPAN_ROW_LOAD_POLICY
 #define SPAN_ROW_LOAD_POLICY 2  // (a measurement build overrides it to time the other policies)
 #endif
@@ -357,7 +379,7 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int 
 #endif
 constexpr int waves_per_simd(int nq) { return nq == 1 ? 8 : (nq == 2 ? 6 : (nq == 4 ? 4 : SPAN_MQ_WAVES)); }
 
-template <class Elt, int D, bool kDense, int U, int NQ, class Args>
+template <class Elt, int D, bool kDense, int U, int NQ, class Args, bool kBoost = false>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(waves_per_simd(NQ), waves_per_simd(NQ)))) void decode_kernel(
     const Args a) {
   constexpr int EPL = Elt::kPerVec;        // elements per lane (one 128-bit piece)
@@ -938,6 +960,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(waves_
 
   // ---- step 3: stream the window's K and V rows, online softmax per row group -------------------
   for (int base = 0; base < wn; base += RPL * U) {
+    if constexpr (kBoost) {  // (wave-uniform: set at the first batch, reset at the second)
+      if (w0 + base <= RPL * U) first_batch_priority(w0 + base == 0);
+    }
     u32x4 kr[U], vr[U];
     bool ok[U];
 #pragma unroll
@@ -1308,24 +1333,30 @@ int launch_typed(const LaunchArgsTable& a, const RunTables* runs, GridMode mode,
 #else
   constexpr int kInFlight = NQ == 16 ? SPAN_MQ_TILES /* tiles of 16 rows */ : (kRowsPerLoad >= 8 ? 2 : 4) / (NQ > 1 ? 2 : 1);
 #endif
+  // short slices of 16-bit rows, one token: the instances that send a wave's first batch at raised priority
+  constexpr bool kCanBoost = NQ == 1 && Elt::kBytes == 2 && SPAN_FIRST_BATCH_PRIORITY > 0;
+  const bool boost = kCanBoost && a.slice_tokens <= kBoostUpToBatches * kWavesPerBlock * kRowsPerLoad * kInFlight;
   if (mode == GridMode::kRuns) {
     if constexpr (!kDense) {
       const dim3 grid((unsigned)a.heads, (unsigned)a.total_slices, 1u);
       LaunchArgsRuns ra;
       static_cast<LaunchArgs&>(ra) = static_cast<const LaunchArgs&>(a);
       ra.r = *runs;
-      hipLaunchKernelGGL((decode_kernel<Elt, D, false, kInFlight, NQ, LaunchArgsRuns>), grid, dim3(kThreads), 0, stream, ra);
+      if (boost) hipLaunchKernelGGL((decode_kernel<Elt, D, false, kInFlight, NQ, LaunchArgsRuns, kCanBoost>), grid, dim3(kThreads), 0, stream, ra);
+      else hipLaunchKernelGGL((decode_kernel<Elt, D, false, kInFlight, NQ, LaunchArgsRuns>), grid, dim3(kThreads), 0, stream, ra);
     } else {
       return SPAN_ERR_SHAPE;  // (not reachable: the dense form never plans runs)
     }
   } else if (mode == GridMode::kTable) {
     const dim3 grid((unsigned)a.heads, (unsigned)a.total_slices, 1u);
-    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsTable>), grid, dim3(kThreads), 0, stream, a);
+    if (boost) hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsTable, kCanBoost>), grid, dim3(kThreads), 0, stream, a);
+    else hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsTable>), grid, dim3(kThreads), 0, stream, a);
   } else {
     const dim3 grid((unsigned)a.heads, (unsigned)a.num_splits, (unsigned)batch);
     LaunchArgsPlain plain;
     static_cast<LaunchArgs&>(plain) = static_cast<const LaunchArgs&>(a);
-    hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsPlain>), grid, dim3(kThreads), 0, stream, plain);
+    if (boost) hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsPlain, kCanBoost>), grid, dim3(kThreads), 0, stream, plain);
+    else hipLaunchKernelGGL((decode_kernel<Elt, D, kDense, kInFlight, NQ, LaunchArgsPlain>), grid, dim3(kThreads), 0, stream, plain);
   }
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) {

@@ -315,9 +315,10 @@ __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? l
 // (per-workgroup stamps: first rows after 4 us for the first quarter of a launch, after 15-18 us for the last) and
 // the launch ends on a thin tail of late starters.  Measured on batch 64 x ~155 positions: 27.67 -> 27.11 us; raising
 // the priority for the start-up chain as well, or by progress through the rows, gains less or loses.  One-token
-// kernels for 16-bit rows only, and only launches whose slices hold up to four batches of rows per wave (kBoost
+// kernels for 16-bit rows of 128 only, and only launches whose slices hold up to four batches of rows per wave (kBoost
 // instances, chosen by the launcher): the passes that serve several tokens lose by it (3 tokens: 31.9 -> 33.6 us), fp32
-// rows at the same shape (5 batches) lose 1 %, 9 batches (batch 8 x 300..2000) lose 0.5 %, 16 and more gain nothing;
+// rows at the same shape (5 batches) lose 1 %, 16-bit rows of 64 lose 6 %, 9 batches (batch 8 x 300..2000) lose 0.5 %,
+// 16 and more gain nothing;
 // even the untaken branch in the loop costs the longer streams 0.5 %, hence instances of their own.
 #ifndef SPAN_FIRST_BATCH_PRIORITY
 #define SPAN_FIRST_BATCH_PRIORITY 3  // (a measurement build sets 0 to time the default arbitration)
@@ -1334,7 +1335,7 @@ int launch_typed(const LaunchArgsTable& a, const RunTables* runs, GridMode mode,
   constexpr int kInFlight = NQ == 16 ? SPAN_MQ_TILES /* tiles of 16 rows */ : (kRowsPerLoad >= 8 ? 2 : 4) / (NQ > 1 ? 2 : 1);
 #endif
   // short slices of 16-bit rows, one token: the instances that send a wave's first batch at raised priority
-  constexpr bool kCanBoost = NQ == 1 && Elt::kBytes == 2 && SPAN_FIRST_BATCH_PRIORITY > 0;
+  constexpr bool kCanBoost = NQ == 1 && Elt::kBytes == 2 && D == 128 && SPAN_FIRST_BATCH_PRIORITY > 0;
   const bool boost = kCanBoost && a.slice_tokens <= kBoostUpToBatches * kWavesPerBlock * kRowsPerLoad * kInFlight;
   if (mode == GridMode::kRuns) {
     if constexpr (!kDense) {

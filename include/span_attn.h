@@ -201,8 +201,8 @@ int dense_decode_attn_append(const span_attn_desc_t* desc, const void* q, const 
  *   q, k_new, v_new : device, desc->dtype, [batch, q_len, heads, head_dim]
  *   out             : device fp32 [batch, q_len, heads, head_dim]
  * Within a launch the rows of that launch's tokens are taken from k_new / v_new, never re-read from the
- * cache; more than four tokens take ceil(q_len / 4) launches on the stream, each appending its own
- * tokens' rows, which the later ones then read from the cache.
+ * cache; more tokens than one pass serves (16 or 4, see span_decode_attn_multi) take several launches on
+ * the stream, each appending its own tokens' rows, which the later ones then read from the cache.
  */
 int span_decode_attn_multi_append(const span_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
                                   void* k_cache, void* v_cache, const int32_t* append_pos,

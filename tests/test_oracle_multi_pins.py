@@ -62,6 +62,27 @@ def test_multi_equals_library_sdpa_with_mask():
         np.testing.assert_allclose(got[b], ref.permute(1, 0, 2).numpy(), rtol=0, atol=TIGHT)
 
 
+def test_many_tokens_equal_library_sdpa_with_mask():
+    """Eighteen query tokens (more than any pass of the GPU path serves at once), limits running through two
+    intervals and a gap: every row against torch's float64 attention under the span-and-causal mask."""
+    rng = np.random.default_rng(15)
+    B, Qn, H, L, D = 2, 18, 3, 64, 12
+    per_seq = [[(0, 5), (20, 33), (40, 64)], [(3, 30), (45, 58)]]
+    q_pos = np.array([28, 41], np.int32)      # limits 28..45 and 41..58
+    q, K, V = _rand(rng, B, Qn, H, L, D)
+    off, st, en = _spans(per_seq)
+    scale = np.float32(0.17)
+    got = oracle.span_attn_multi(q, K, V, off, st, en, q_pos, scale)
+    bits = _attend_bits(per_seq, q_pos, Qn, L)
+    assert bits.any(axis=2).all()
+    for b in range(B):
+        tq = torch.from_numpy(q[b]).double().permute(1, 0, 2)
+        tk, tv = torch.from_numpy(K[b]).double(), torch.from_numpy(V[b]).double()
+        mask = torch.from_numpy(bits[b])[None, :, :]
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=float(scale))
+        np.testing.assert_allclose(got[b], ref.permute(1, 0, 2).numpy(), rtol=0, atol=TIGHT)
+
+
 def test_multi_equals_bruteforce_additive_mask():
     rng = np.random.default_rng(12)
     B, Qn, H, L, D = 3, 3, 2, 41, 8
